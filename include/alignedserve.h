@@ -1,0 +1,221 @@
+/*
+ * alignedserve.h -- C ABI of the MI355X (gfx950) decode-attention hot path of
+ * AlignedServe: length-aligned batch formation, host-to-HBM staging of a
+ * batch's paged KV blocks, and batched single-query attention over the paged
+ * KV cache for requests of different KV length.
+ *
+ * Conventions that hold for every entry point
+ *   - plain C types only; "device" pointers are HIP device pointers owned by
+ *     the caller, "host" pointers are ordinary host memory unless stated to
+ *     be pinned;
+ *   - the library never allocates or frees caller-visible memory;
+ *   - every call returns an as_status and never throws; on failure nothing
+ *     has been enqueued unless the status is AS_EHIP, and as_last_error()
+ *     returns a thread-local, library-owned description;
+ *   - calls that take a stream are asynchronous on it and return after
+ *     enqueueing; a null stream is the HIP default stream.
+ *
+ * Paged KV layout (the library's contract; the paper only speaks of "memory
+ * blocks", Section 3.3):
+ *   k_blocks, v_blocks : [num_blocks][num_kv_heads][block_size][head_dim]
+ *                        row-major, block_size == 16, fp32 or bf16;
+ *   block_table        : int32 [batch][max_blocks_per_seq];
+ *   logical token t of request b is row t % 16 of physical block
+ *   block_table[b][t / 16].  Rows at or past kv_lens[b] in a request's last
+ *   block, unused block_table entries and blocks nobody owns are don't-care:
+ *   they may hold NaN/Inf and never influence a result.
+ */
+#ifndef ALIGNEDSERVE_H
+#define ALIGNEDSERVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AS_OK = 0,
+  AS_EINVAL = 1,       /* null pointer, non-positive size, inconsistent shape   */
+  AS_ERANGE = 2,       /* a value outside what the arguments allow              */
+  AS_EWORKSPACE = 3,   /* workspace smaller than as_decode_attention_workspace  */
+  AS_EUNSUPPORTED = 4, /* dtype / head_dim / block_size the kernels do not have */
+  AS_EHIP = 5          /* a HIP runtime call failed (message has its string)    */
+} as_status;
+
+#define AS_DTYPE_F32 0
+#define AS_DTYPE_BF16 1
+
+/* Library version (major*10000 + minor*100 + patch). */
+int32_t as_version(void);
+
+/* Description of the last failure on the calling thread ("" if none). */
+const char* as_last_error(void);
+
+/* --------------------------------------------------------------------------
+ * Batch formation (host only; no GPU is touched).
+ *
+ * The paper's prefix-aware batching (Sections 2.4 and 3.3) groups requests
+ * whose prefixes have similar length, because a decode iteration lasts as
+ * long as its longest member (Section 2.3).  With a fixed batch size this is
+ * the partition into ceil(n / batch_size) batches that minimises the sum of
+ * per-batch maximum KV lengths; sorting by length and cutting consecutive
+ * chunks reaches it.  Canonical result:
+ *   order          request indices sorted by (kv_len descending, index
+ *                  ascending), int32[n], caller-allocated;
+ *   batch_offsets  int32[ceil(n/batch_size) + 1], caller-allocated; batch j is
+ *                  order[batch_offsets[j] .. batch_offsets[j+1]); all batches
+ *                  hold batch_size requests except possibly the last, which
+ *                  then holds the shortest ones;
+ *   num_batches    ceil(n / batch_size) (0 when n == 0; batch_offsets = {0}).
+ * kv_lens: host int32[n], each >= 1.  All pointers are host pointers.
+ * Errors: AS_EINVAL for null pointers (kv_lens/order may be null only when
+ * n == 0), n < 0, batch_size <= 0 or a kv_len < 1.
+ * -------------------------------------------------------------------------- */
+as_status as_aligned_batch(const int32_t* kv_lens, int32_t n, int32_t batch_size,
+                           int32_t* order, int32_t* batch_offsets, int32_t* num_batches);
+
+/* --------------------------------------------------------------------------
+ * Decode-iteration attention (paper Section 2.2, Eq. 2):
+ *   out[b][h] = softmax(q[b][h] . K_b^T / sqrt(d_k)) V_b
+ * for the newest token's query of every request b against all kv_lens[b]
+ * cached keys / values of that request (the newest token's own k, v are
+ * already in the cache; there is no causal mask).  Query head h reads KV head
+ * h / (num_q_heads / num_kv_heads).  Accumulation is fp32.
+ * -------------------------------------------------------------------------- */
+typedef struct {
+  int32_t dtype;              /* AS_DTYPE_* of q, k_blocks, v_blocks                */
+  int32_t out_dtype;          /* AS_DTYPE_* of out                                   */
+  int32_t batch;              /* B >= 1                                              */
+  int32_t num_q_heads;        /* multiple of num_kv_heads                            */
+  int32_t num_kv_heads;
+  int32_t head_dim;           /* 64 or 128                                           */
+  int32_t block_size;         /* must be 16                                          */
+  int32_t num_blocks;         /* pool size; block ids are clamped into [0, this)     */
+  int32_t max_blocks_per_seq; /* row stride of block_table                           */
+  float scale;                /* 0 => 1/sqrt(head_dim)                               */
+  int32_t chunk_tokens;       /* split-KV granularity in tokens: a request's KV is
+                                 cut into chunks of this many tokens, one workgroup
+                                 each, merged exactly afterwards.  0 => chosen by
+                                 the library.  Otherwise a multiple of 16 in
+                                 [16, 4096].                                         */
+  int32_t flags;              /* AS_ATTN_* bits                                      */
+} as_attn_params;
+
+/* The work plan in `workspace` was written by an earlier call with the same
+ * kv_lens, batch, chunk_tokens and head counts (e.g. the previous layer of
+ * the same decode iteration): skip rebuilding it. */
+#define AS_ATTN_REUSE_PLAN 1
+/* Force the vector-ALU kernel even where the matrix-core (MFMA) kernel would
+ * be selected for grouped-query shapes. */
+#define AS_ATTN_NO_MFMA 2
+
+/* Bytes of device workspace as_decode_attention needs for these parameters
+ * when the batch holds at most total_kv_tokens tokens in all (sum of
+ * kv_lens) AND the call passes kv_lens_host.  Pass total_kv_tokens < 0 to
+ * size for the worst case batch * max_blocks_per_seq * 16, which also covers
+ * calls without kv_lens_host.  Returns 0 on invalid parameters. */
+size_t as_decode_attention_workspace(const as_attn_params* p, int64_t total_kv_tokens);
+
+/* q            device [batch][num_q_heads][head_dim], dtype
+ * k_blocks     device paged pool (layout above), dtype
+ * v_blocks     device paged pool, dtype
+ * block_table  device int32 [batch][max_blocks_per_seq]
+ * kv_lens      device int32 [batch]; a request with kv_len <= 0 gets zeros
+ * kv_lens_host optional host copy of kv_lens (may be null).  When given the
+ *              launch is sized exactly and the lengths are validated
+ *              (1 <= kv_len <= max_blocks_per_seq * 16) before anything is
+ *              enqueued; when null the launch is sized for the worst case
+ *              and nothing is validated.
+ * out          device [batch][num_q_heads][head_dim], out_dtype
+ * workspace    device scratch of at least as_decode_attention_workspace()
+ *              bytes, 256-byte aligned; its contents are only meaningful to
+ *              the library (plan + split-KV partials) and may be reused by
+ *              the next call.
+ * Inputs are read-only; out and workspace are the only memory written.
+ * Device-side contents of block_table are not validated on the hot path;
+ * ids are clamped into the pool so that a bad id yields a wrong result, not
+ * a fault.  Two calls sharing one workspace must be ordered on one stream.
+ * Errors: AS_EINVAL, AS_ERANGE (host lens out of range), AS_EUNSUPPORTED,
+ * AS_EWORKSPACE, AS_EHIP. */
+as_status as_decode_attention(const void* q, const void* k_blocks, const void* v_blocks,
+                              const int32_t* block_table, const int32_t* kv_lens,
+                              const int32_t* kv_lens_host, void* out,
+                              const as_attn_params* p, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
+/* --------------------------------------------------------------------------
+ * KV staging: host KV pool -> HBM block pool (paper Section 3.2: the KV pool
+ * lives in host memory and a scheduled batch's KVCache is migrated to the
+ * decoding GPU, directly over PCIe when no peer GPU serves as a buffer; the
+ * batch to run next is prefetched asynchronously, Fig. 4 step 4, so that the
+ * transfer overlaps the running batch's decoding, Section 4.4).
+ *
+ * Enqueues, on `hip_stream`, copies of m blocks of block_bytes bytes each:
+ *   host_k + src_ids[i] * block_bytes  ->  dev_k + dst_ids[i] * block_bytes
+ * and the same for host_v -> dev_v (host_v/dev_v may both be null to move one
+ * pool only).  Runs in which src and dst ids both advance by one are merged
+ * into a single copy.  host_* must be pinned (hipHostMalloc) memory; the id
+ * arrays are host arrays and are consumed before the call returns.
+ * num_src_blocks / num_dst_blocks bound the ids.  The caller orders the
+ * copies against consumers with events (see as_pipeline_* below).
+ * Errors: AS_EINVAL (null, m < 0, block_bytes == 0 or not a multiple of 16,
+ * unpinned host pointer), AS_ERANGE (an id out of range), AS_EHIP.
+ * -------------------------------------------------------------------------- */
+as_status as_stage_kv(const void* host_k, const void* host_v, const int64_t* src_ids,
+                      int64_t num_src_blocks, void* dev_k, void* dev_v,
+                      const int32_t* dst_ids, int32_t num_dst_blocks, int32_t m,
+                      size_t block_bytes, void* hip_stream);
+
+/* The reverse direction (eviction of a request's blocks to the host pool,
+ * Section 3.4 case 3): dev + src_ids[i] -> host + dst_ids[i]. */
+as_status as_unstage_kv(void* host_k, void* host_v, const int64_t* dst_ids,
+                        int64_t num_host_blocks, const void* dev_k, const void* dev_v,
+                        const int32_t* src_ids, int32_t num_dev_blocks, int32_t m,
+                        size_t block_bytes, void* hip_stream);
+
+/* --------------------------------------------------------------------------
+ * Copy / compute handshake for a multi-buffered HBM block pool (paper
+ * Section 4.4: batch generation and prefetch are pipelined with decoding).
+ * The pipeline owns one side stream (default priority) and, per buffer, a
+ * "ready" event (copies into the buffer are complete) and a "free" event
+ * (the last attention that read the buffer is complete).
+ *   as_pipeline_create   num_buffers in [1, 8]
+ *   as_pipeline_stream   the side stream, to pass to as_stage_kv
+ *   as_pipeline_begin_stage(buf)    side stream waits for buf's "free"
+ *   as_pipeline_end_stage(buf)      records buf's "ready" on the side stream
+ *   as_pipeline_acquire(buf, s)     stream s waits for buf's "ready"
+ *   as_pipeline_release(buf, s)     records buf's "free" on stream s
+ *   as_pipeline_destroy  synchronises the side stream, destroys everything
+ * Errors: AS_EINVAL (null pipeline, buf out of range), AS_EHIP.
+ * -------------------------------------------------------------------------- */
+typedef struct as_pipeline as_pipeline;
+as_status as_pipeline_create(as_pipeline** out, int32_t num_buffers);
+void* as_pipeline_stream(as_pipeline* p);
+as_status as_pipeline_begin_stage(as_pipeline* p, int32_t buf);
+as_status as_pipeline_end_stage(as_pipeline* p, int32_t buf);
+as_status as_pipeline_acquire(as_pipeline* p, int32_t buf, void* hip_stream);
+as_status as_pipeline_release(as_pipeline* p, int32_t buf, void* hip_stream);
+as_status as_pipeline_destroy(as_pipeline* p);
+
+/* --------------------------------------------------------------------------
+ * Measurement aid: streams every K and V byte the attention call with the
+ * same arguments would read (same block table, same lengths, same work
+ * split) and folds them into a checksum, with no other arithmetic.  Its
+ * bandwidth is the ceiling the attention kernel is compared with.
+ * checksum: device uint32[256], XOR-accumulated with atomics (slot = workgroup
+ * index mod 256); the XOR of the 256 slots equals the XOR of every 32-bit
+ * word of every K and V block the batch references (whole blocks), for the
+ * slots' initial contents zero.  Same errors as as_decode_attention.
+ * -------------------------------------------------------------------------- */
+as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks,
+                           const int32_t* block_table, const int32_t* kv_lens,
+                           const int32_t* kv_lens_host, uint32_t* checksum,
+                           const as_attn_params* p, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALIGNEDSERVE_H */

@@ -1,0 +1,273 @@
+"""Thin ctypes binding over the C-ABI library (include/alignedserve.h).
+
+Argument marshalling only: every step of the hot path runs inside the
+library.  PyTorch tensors are used as device memory (their data_ptr() is
+handed over) and torch streams as HIP streams.  There is no fallback: if the
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libalignedserve.so")
+
+AS_OK, AS_EINVAL, AS_ERANGE, AS_EWORKSPACE, AS_EUNSUPPORTED, AS_EHIP = range(6)
+STATUS_NAMES = {0: "AS_OK", 1: "AS_EINVAL", 2: "AS_ERANGE", 3: "AS_EWORKSPACE",
+                4: "AS_EUNSUPPORTED", 5: "AS_EHIP"}
+DTYPE_F32, DTYPE_BF16 = 0, 1
+ATTN_REUSE_PLAN, ATTN_NO_MFMA = 1, 2
+
+EXPORTS = [
+    "as_version", "as_last_error", "as_aligned_batch", "as_decode_attention_workspace",
+    "as_decode_attention", "as_stage_kv", "as_unstage_kv", "as_pipeline_create",
+    "as_pipeline_stream", "as_pipeline_begin_stage", "as_pipeline_end_stage",
+    "as_pipeline_acquire", "as_pipeline_release", "as_pipeline_destroy", "as_kv_read_sweep",
+]
+
+
+class AttnParams(C.Structure):
+    _fields_ = [
+        ("dtype", C.c_int32), ("out_dtype", C.c_int32), ("batch", C.c_int32),
+        ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("block_size", C.c_int32), ("num_blocks", C.c_int32), ("max_blocks_per_seq", C.c_int32),
+        ("scale", C.c_float), ("chunk_tokens", C.c_int32), ("flags", C.c_int32),
+    ]
+
+
+class AlignedServeError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load the built library; raises if it is missing (no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2605_23389_amd.build` "
+            "(hipcc, gfx950). There is no CPU or PyTorch fallback for the hot path.")
+    lib = C.CDLL(LIB_PATH)
+    i32p, i64p, vp = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.c_void_p
+    lib.as_version.restype = C.c_int32
+    lib.as_last_error.restype = C.c_char_p
+    lib.as_aligned_batch.restype = C.c_int
+    lib.as_aligned_batch.argtypes = [i32p, C.c_int32, C.c_int32, i32p, i32p, i32p]
+    lib.as_decode_attention_workspace.restype = C.c_size_t
+    lib.as_decode_attention_workspace.argtypes = [C.POINTER(AttnParams), C.c_int64]
+    lib.as_decode_attention.restype = C.c_int
+    lib.as_decode_attention.argtypes = [vp, vp, vp, vp, vp, i32p, vp, C.POINTER(AttnParams), vp,
+                                        C.c_size_t, vp]
+    lib.as_kv_read_sweep.restype = C.c_int
+    lib.as_kv_read_sweep.argtypes = [vp, vp, vp, vp, i32p, vp, C.POINTER(AttnParams), vp,
+                                     C.c_size_t, vp]
+    lib.as_stage_kv.restype = C.c_int
+    lib.as_stage_kv.argtypes = [vp, vp, i64p, C.c_int64, vp, vp, i32p, C.c_int32, C.c_int32,
+                                C.c_size_t, vp]
+    lib.as_unstage_kv.restype = C.c_int
+    lib.as_unstage_kv.argtypes = [vp, vp, i64p, C.c_int64, vp, vp, i32p, C.c_int32, C.c_int32,
+                                  C.c_size_t, vp]
+    lib.as_pipeline_create.restype = C.c_int
+    lib.as_pipeline_create.argtypes = [C.POINTER(vp), C.c_int32]
+    lib.as_pipeline_stream.restype = vp
+    lib.as_pipeline_stream.argtypes = [vp]
+    for name in ("as_pipeline_begin_stage", "as_pipeline_end_stage"):
+        getattr(lib, name).restype = C.c_int
+        getattr(lib, name).argtypes = [vp, C.c_int32]
+    for name in ("as_pipeline_acquire", "as_pipeline_release"):
+        getattr(lib, name).restype = C.c_int
+        getattr(lib, name).argtypes = [vp, C.c_int32, vp]
+    lib.as_pipeline_destroy.restype = C.c_int
+    lib.as_pipeline_destroy.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != AS_OK:
+        raise AlignedServeError(status, load().as_last_error().decode("utf-8", "replace"))
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: Optional[np.ndarray], ctype):
+    return None if a is None else a.ctypes.data_as(C.POINTER(ctype))
+
+
+def version() -> int:
+    return int(load().as_version())
+
+
+# ---------------------------------------------------------------------------
+# aligned_batch
+# ---------------------------------------------------------------------------
+def aligned_batch(kv_lens, batch_size: int):
+    """Length-aligned batches.  Returns (order int32[n], batch_offsets
+    int32[num_batches + 1])."""
+    lib = load()
+    lens = _i32(kv_lens)
+    n = int(lens.shape[0])
+    nb_cap = (n + max(int(batch_size), 1) - 1) // max(int(batch_size), 1)
+    order = np.empty(max(n, 1), dtype=np.int32)
+    offsets = np.empty(nb_cap + 1, dtype=np.int32)
+    nb = C.c_int32(0)
+    _check(lib.as_aligned_batch(_ptr(lens, C.c_int32), n, int(batch_size), _ptr(order, C.c_int32),
+                                _ptr(offsets, C.c_int32), C.byref(nb)))
+    return order[:n], offsets[: nb.value + 1]
+
+
+# ---------------------------------------------------------------------------
+# decode_attention
+# ---------------------------------------------------------------------------
+def _torch_dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    raise AlignedServeError(AS_EUNSUPPORTED, f"tensor dtype {t.dtype}")
+
+
+def attn_params(q, k_blocks, block_table, out, scale: float = 0.0, chunk_tokens: int = 0,
+                flags: int = 0) -> AttnParams:
+    B, Hq, D = q.shape
+    NB, Hkv, bs, D2 = k_blocks.shape
+    assert D == D2
+    return AttnParams(dtype=_torch_dtype_code(k_blocks), out_dtype=_torch_dtype_code(out), batch=B,
+                      num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, block_size=bs, num_blocks=NB,
+                      max_blocks_per_seq=block_table.shape[1], scale=float(scale),
+                      chunk_tokens=int(chunk_tokens), flags=int(flags))
+
+
+def decode_attention_workspace(params: AttnParams, total_kv_tokens: int = -1) -> int:
+    return int(load().as_decode_attention_workspace(C.byref(params), int(total_kv_tokens)))
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def decode_attention(q, k_blocks, v_blocks, block_table, kv_lens, out, kv_lens_host=None,
+                     workspace=None, scale: float = 0.0, chunk_tokens: int = 0, flags: int = 0,
+                     stream=None, params: Optional[AttnParams] = None):
+    """Enqueue decode attention for one batch.  All tensor arguments are
+    torch CUDA tensors (contiguous); kv_lens_host is an optional int32 NumPy
+    array.  `workspace` is a torch uint8 CUDA tensor; one is allocated when
+    omitted (callers on a hot loop pass their own).  Returns `out`."""
+    import torch
+    lib = load()
+    for t in (q, k_blocks, v_blocks, block_table, kv_lens, out):
+        if not t.is_cuda or not t.is_contiguous():
+            raise AlignedServeError(AS_EINVAL, "tensors must be contiguous CUDA tensors")
+    if block_table.dtype != torch.int32 or kv_lens.dtype != torch.int32:
+        raise AlignedServeError(AS_EINVAL, "block_table and kv_lens must be int32")
+    if q.dtype != k_blocks.dtype or v_blocks.dtype != k_blocks.dtype or v_blocks.shape != k_blocks.shape:
+        raise AlignedServeError(AS_EINVAL, "q / k_blocks / v_blocks disagree in dtype or shape")
+    if out.shape != q.shape or kv_lens.shape[0] != q.shape[0] or block_table.shape[0] != q.shape[0]:
+        raise AlignedServeError(AS_EINVAL, "out / kv_lens / block_table disagree with q in shape")
+    if params is None:
+        params = attn_params(q, k_blocks, block_table, out, scale, chunk_tokens, flags)
+    host = None
+    if kv_lens_host is not None:
+        host = _i32(kv_lens_host)
+        if host.shape[0] != q.shape[0]:
+            raise AlignedServeError(AS_EINVAL, "kv_lens_host has the wrong length")
+    if workspace is None:
+        total = int(host.sum()) if host is not None else -1
+        nbytes = decode_attention_workspace(params, total)
+        if nbytes == 0:
+            _check(AS_EINVAL if not lib.as_last_error() else AS_EINVAL)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+    _check(lib.as_decode_attention(q.data_ptr(), k_blocks.data_ptr(), v_blocks.data_ptr(),
+                                   block_table.data_ptr(), kv_lens.data_ptr(),
+                                   _ptr(host, C.c_int32), out.data_ptr(), C.byref(params),
+                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out
+
+
+def kv_read_sweep(k_blocks, v_blocks, block_table, kv_lens, checksum, params: AttnParams,
+                  workspace, kv_lens_host=None, stream=None):
+    """Measurement aid: stream the K/V bytes the attention call would read."""
+    host = None if kv_lens_host is None else _i32(kv_lens_host)
+    _check(load().as_kv_read_sweep(k_blocks.data_ptr(), v_blocks.data_ptr(), block_table.data_ptr(),
+                                   kv_lens.data_ptr(), _ptr(host, C.c_int32), checksum.data_ptr(),
+                                   C.byref(params), workspace.data_ptr(), workspace.numel(),
+                                   _stream_ptr(stream)))
+
+
+# ---------------------------------------------------------------------------
+# stage_kv / unstage_kv / pipeline
+# ---------------------------------------------------------------------------
+def _move(fn, host_k, host_v, host_ids, dev_k, dev_v, dev_ids, block_bytes, stream):
+    hid = np.ascontiguousarray(host_ids, dtype=np.int64)
+    did = _i32(dev_ids)
+    if hid.shape != did.shape:
+        raise AlignedServeError(AS_EINVAL, "id lists differ in length")
+    n_host = host_k.numel() * host_k.element_size() // block_bytes
+    n_dev = dev_k.numel() * dev_k.element_size() // block_bytes
+    _check(fn(host_k.data_ptr(), None if host_v is None else host_v.data_ptr(),
+              _ptr(hid, C.c_int64), n_host, dev_k.data_ptr(),
+              None if dev_v is None else dev_v.data_ptr(), _ptr(did, C.c_int32), n_dev,
+              int(hid.shape[0]), int(block_bytes), _stream_ptr(stream)))
+
+
+def stage_kv(host_k, host_v, src_ids, dev_k, dev_v, dst_ids, block_bytes: int, stream=None):
+    """Enqueue host-pool -> HBM-pool block copies (host tensors pinned)."""
+    _move(load().as_stage_kv, host_k, host_v, src_ids, dev_k, dev_v, dst_ids, block_bytes, stream)
+
+
+def unstage_kv(host_k, host_v, dst_ids, dev_k, dev_v, src_ids, block_bytes: int, stream=None):
+    """Enqueue HBM-pool -> host-pool block copies (eviction)."""
+    _move(load().as_unstage_kv, host_k, host_v, dst_ids, dev_k, dev_v, src_ids, block_bytes, stream)
+
+
+class Pipeline:
+    """Copy/compute handshake of a multi-buffered HBM block pool."""
+
+    def __init__(self, num_buffers: int = 2):
+        self._h = C.c_void_p()
+        _check(load().as_pipeline_create(C.byref(self._h), int(num_buffers)))
+
+    @property
+    def stream(self) -> int:
+        return int(load().as_pipeline_stream(self._h))
+
+    def begin_stage(self, buf: int):
+        _check(load().as_pipeline_begin_stage(self._h, buf))
+
+    def end_stage(self, buf: int):
+        _check(load().as_pipeline_end_stage(self._h, buf))
+
+    def acquire(self, buf: int, stream=None):
+        _check(load().as_pipeline_acquire(self._h, buf, _stream_ptr(stream)))
+
+    def release(self, buf: int, stream=None):
+        _check(load().as_pipeline_release(self._h, buf, _stream_ptr(stream)))
+
+    def destroy(self):
+        if self._h:
+            h, self._h = self._h, C.c_void_p()
+            _check(load().as_pipeline_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,792 @@
+// Batched decode-iteration attention over a paged KV cache, gfx950 (MI355X).
+//
+// Computes paper Section 2.2 Eq. 2, softmax(q K^T / sqrt(d_k)) V, for one
+// query per (request, query head) against that request's kv_len cached keys
+// and values.  Per Table 1 the work moves 2*s*h KV elements per token and
+// performs as many multiply-adds: it is bound by HBM bandwidth, so the kernel
+// is organised around streaming every K/V byte exactly once with fully
+// coalesced 128-bit loads and enough of them in flight, not around a GEMM.
+//
+// Work split.  A request's KV sequence is cut into chunks of `chunk_tokens`
+// tokens.  One workgroup (4 wavefronts) handles one (request, chunk, KV head)
+// item; items of all requests are flattened into one list so that the time of
+// a launch follows the total token count of the batch, not batch * longest
+// request.  The plan kernel builds that list on the device from kv_lens.
+// Chunks of one request are merged exactly afterwards (combine kernel); a
+// request that fits one chunk is finished by its workgroup directly.
+//
+// Inside a workgroup.  A tile is one 16-token block of one KV head: a
+// contiguous [16][D] slab.  A wavefront owns every 4th tile of the chunk.
+// One 128-bit load per lane covers 1 KiB of the slab: LPT = D*sizeof(T)/16
+// lanes share a token, so a load instruction brings 64/LPT tokens and the
+// wave runs 64/LPT independent online-softmax streams ("token groups").  The
+// q.k partial products are summed over the LPT lanes with DPP row operations
+// (no LDS traffic); p.v needs no cross-lane step because each lane keeps the
+// output dimensions it loaded.  K/V tiles are double-buffered in registers:
+// the loads of tile j+1 are issued before tile j is consumed.  With G query
+// heads per KV head (grouped-query attention) one K/V tile in registers
+// serves all G heads.  At the end the token groups of a wave are merged with
+// cross-lane shuffles, the 4 waves through LDS.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "common.h"
+
+namespace {
+
+constexpr int kBlock = 16;      // tokens per KV block
+constexpr int kWaves = 4;       // wavefronts per workgroup
+constexpr int kThreads = 64 * kWaves;
+constexpr int kMaxChunk = 64 * kWaves * kBlock;  // one block id per lane per wave
+constexpr float kNegInf = -__builtin_huge_valf();
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+struct bf16_t { uint16_t bits; };
+
+template <typename T> struct Elem;
+template <> struct Elem<float> { static constexpr int kPerLoad = 4; };
+template <> struct Elem<bf16_t> { static constexpr int kPerLoad = 8; };
+
+// ------------------------------------------------------------------ workspace
+// [0,256)            PlanHeader
+// cu_chunks          int32[batch + 1]   first item of each request
+// items              int2[max_items]    (request, chunk index)
+// part_ml            float2[max_items * H_q]   (running max in log2 units, sum)
+// part_acc           float[max_items * H_q * D]
+struct PlanHeader {
+  int32_t total_items;
+  int32_t pad[63];
+};
+
+struct WorkspaceLayout {
+  size_t cu_off, items_off, ml_off, acc_off, total;
+  int64_t max_items;
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+WorkspaceLayout layout_for(const as_attn_params& p, int64_t max_items) {
+  WorkspaceLayout w;
+  w.max_items = max_items;
+  w.cu_off = sizeof(PlanHeader);
+  w.items_off = align256(w.cu_off + sizeof(int32_t) * (static_cast<size_t>(p.batch) + 1));
+  w.ml_off = align256(w.items_off + sizeof(int2) * static_cast<size_t>(w.max_items));
+  w.acc_off = align256(w.ml_off + sizeof(float2) * static_cast<size_t>(w.max_items) * p.num_q_heads);
+  w.total = align256(w.acc_off + sizeof(float) * static_cast<size_t>(w.max_items) * p.num_q_heads *
+                                     p.head_dim);
+  return w;
+}
+
+// ------------------------------------------------------------------ plan
+// One workgroup.  cu_chunks = exclusive scan of per-request chunk counts
+// (a request with kv_len <= 0 still gets one item, which writes zeros), then
+// item i -> (request, chunk) by binary search in cu_chunks.
+__global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ kv_lens, int batch,
+                                                   int chunk, int max_len, PlanHeader* __restrict__ hdr,
+                                                   int32_t* __restrict__ cu_chunks,
+                                                   int2* __restrict__ items, int64_t max_items) {
+  __shared__ int32_t part[256];
+  const int tid = threadIdx.x;
+  const int per = (batch + 255) / 256;
+  const int lo = tid * per;
+  const int hi = min(batch, lo + per);
+  int32_t sum = 0;
+  for (int b = lo; b < hi; ++b) {
+    const int32_t L = min(kv_lens[b], max_len);
+    sum += L > 0 ? (L + chunk - 1) / chunk : 1;
+  }
+  part[tid] = sum;
+  __syncthreads();
+  // Hillis-Steele inclusive scan over 256 partial sums
+  for (int off = 1; off < 256; off <<= 1) {
+    int32_t v = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  int32_t run = part[tid] - sum;
+  for (int b = lo; b < hi; ++b) {
+    cu_chunks[b] = run;
+    const int32_t L = min(kv_lens[b], max_len);
+    run += L > 0 ? (L + chunk - 1) / chunk : 1;
+  }
+  const int32_t total = part[255];
+  if (tid == 0) {
+    cu_chunks[batch] = total;
+    hdr->total_items = total;
+  }
+  __syncthreads();  // cu_chunks written by this workgroup is visible to it
+  const int64_t n = total < max_items ? total : max_items;
+  for (int64_t i = tid; i < n; i += 256) {
+    int a = 0, z = batch;  // largest a with cu_chunks[a] <= i
+    while (z - a > 1) {
+      const int mid = (a + z) >> 1;
+      if (cu_chunks[mid] <= i) a = mid; else z = mid;
+    }
+    items[i] = make_int2(a, static_cast<int>(i - cu_chunks[a]));
+  }
+}
+
+// ------------------------------------------------------------------ helpers
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the LPT lanes that share a token; every one of them gets the sum.
+template <int LPT>
+__device__ __forceinline__ float group_sum(float v) {
+  if (LPT >= 2) v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  if (LPT >= 4) v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  if (LPT >= 8) v += dpp_move<0x141>(v);   // row_half_mirror
+  if (LPT >= 16) v += dpp_move<0x140>(v);  // row_mirror
+  if (LPT >= 32) v += __shfl_xor(v, 16);
+  return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xFFFF0000u); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+// dot of the EPL elements a lane holds of one key row with its slice of q
+template <typename T> struct Dot;
+template <> struct Dot<float> {
+  __device__ static __forceinline__ float run(const u32x4& k, const u32x4& q) {
+    float s = __builtin_bit_cast(float, k.x) * __builtin_bit_cast(float, q.x);
+    s = fmaf(__builtin_bit_cast(float, k.y), __builtin_bit_cast(float, q.y), s);
+    s = fmaf(__builtin_bit_cast(float, k.z), __builtin_bit_cast(float, q.z), s);
+    s = fmaf(__builtin_bit_cast(float, k.w), __builtin_bit_cast(float, q.w), s);
+    return s;
+  }
+};
+template <> struct Dot<bf16_t> {
+  // v_dot2c_f32_bf16: two bf16 products accumulated into an fp32 register.
+  // The operands are taken as pairs out of a whole <8 x bf16> value: casting
+  // single 32-bit lanes of the loaded vector to <2 x bf16> makes this
+  // compiler pick lane 0 for every pair.
+  __device__ static __forceinline__ float run(const u32x4& ku, const u32x4& qu) {
+    const bf16x8_t k = __builtin_bit_cast(bf16x8_t, ku);
+    const bf16x8_t q = __builtin_bit_cast(bf16x8_t, qu);
+    float s = 0.f;
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(k, k, 0, 1), __builtin_shufflevector(q, q, 0, 1), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(k, k, 2, 3), __builtin_shufflevector(q, q, 2, 3), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(k, k, 4, 5), __builtin_shufflevector(q, q, 4, 5), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(k, k, 6, 7), __builtin_shufflevector(q, q, 6, 7), s, false);
+    return s;
+  }
+};
+
+// widen the EPL elements of one loaded 128-bit word to fp32
+template <typename T> struct Widen;
+template <> struct Widen<float> {
+  __device__ static __forceinline__ void run(const u32x4& v, float (&o)[4]) {
+    o[0] = __builtin_bit_cast(float, v.x); o[1] = __builtin_bit_cast(float, v.y);
+    o[2] = __builtin_bit_cast(float, v.z); o[3] = __builtin_bit_cast(float, v.w);
+  }
+};
+template <> struct Widen<bf16_t> {
+  __device__ static __forceinline__ void run(const u32x4& v, float (&o)[8]) {
+    o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x); o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
+    o[4] = bf16_lo(v.z); o[5] = bf16_hi(v.z); o[6] = bf16_lo(v.w); o[7] = bf16_hi(v.w);
+  }
+};
+
+__device__ __forceinline__ u32x4 load128(const char* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
+struct AttnArgs {
+  const char* q;
+  const char* k_blocks;
+  const char* v_blocks;
+  const int32_t* block_table;
+  const int32_t* kv_lens;
+  char* out;
+  const PlanHeader* hdr;
+  const int2* items;
+  float2* part_ml;
+  float* part_acc;
+  int32_t num_kv_heads;
+  int32_t head_groups;  // workgroups per item: num_q_heads / G
+  int32_t kv_div;       // head groups per KV head (1 when G covers the whole GQA group)
+  int32_t num_blocks;
+  int32_t max_blocks_per_seq;
+  int32_t chunk;
+  int32_t out_bf16;
+  int32_t exact_grid;  // grid == total_items * num_kv_heads exactly
+  float c;             // scale * log2(e)
+};
+
+// Online-softmax state of one token group for one query head.
+template <int EPL>
+struct HeadState {
+  float m;  // running max of raw q.k (unscaled)
+  float l;  // sum of exp2((s - m) * c)
+  float acc[EPL];
+};
+
+template <typename T, int D, int G, bool MASKED>
+__device__ __forceinline__ void consume_tile(const u32x4 (&kr)[kBlock * D * sizeof(T) / 1024],
+                                             const u32x4 (&vr)[kBlock * D * sizeof(T) / 1024],
+                                             const u32x4 (&qr)[G],
+                                             HeadState<Elem<T>::kPerLoad> (&st)[G], float c,
+                                             int first_token, int kv_len, int lane) {
+  constexpr int EPL = Elem<T>::kPerLoad;
+  constexpr int LPT = D / EPL;
+  constexpr int TPI = 64 / LPT;
+  constexpr int NLD = kBlock / TPI;
+
+  bool valid[NLD];
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) valid[i] = !MASKED || (first_token + i * TPI + lane / LPT < kv_len);
+
+  float vf[NLD][EPL];
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    Widen<T>::run(vr[i], vf[i]);
+    if (MASKED) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) vf[i][e] = valid[i] ? vf[i][e] : 0.f;
+    }
+  }
+
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float s[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      s[i] = group_sum<LPT>(Dot<T>::run(kr[i], qr[g]));
+      if (MASKED) s[i] = valid[i] ? s[i] : kNegInf;
+    }
+    float mx = s[0];
+#pragma unroll
+    for (int i = 1; i < NLD; ++i) mx = fmaxf(mx, s[i]);
+    const float m_new = fmaxf(st[g].m, mx);
+    // a token group that has seen no valid token yet keeps m == -inf; use 0
+    // as the reference there so that no inf - inf is formed
+    const float ref = (MASKED && m_new == kNegInf) ? 0.f : m_new;
+    const float alpha = fast_exp2((st[g].m - ref) * c);
+    const float nref = -ref * c;
+    float p[NLD];
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      p[i] = fast_exp2(fmaf(s[i], c, nref));
+      if (MASKED) p[i] = valid[i] ? p[i] : 0.f;
+      psum += p[i];
+    }
+    st[g].l = fmaf(st[g].l, alpha, psum);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      float a = st[g].acc[e] * alpha;
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) a = fmaf(p[i], vf[i][e], a);
+      st[g].acc[e] = a;
+    }
+    st[g].m = m_new;
+  }
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void load_tile(u32x4 (&r)[kBlock * D * sizeof(T) / 1024], const char* slab,
+                                          int lane) {
+  constexpr int NLD = kBlock * D * sizeof(T) / 1024;
+  const char* p = slab + lane * 16;
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) r[i] = load128(p + i * 1024);
+}
+
+// merge state `o` (from another token group / wave) into `s`; both in raw-max units
+template <int EPL>
+__device__ __forceinline__ void merge_state(HeadState<EPL>& s, float om, float ol, const float (&oacc)[EPL],
+                                            float c) {
+  const float M = fmaxf(s.m, om);
+  const float ref = (M == kNegInf) ? 0.f : M;
+  const float a = fast_exp2((s.m - ref) * c);
+  const float b = fast_exp2((om - ref) * c);
+  s.l = s.l * a + ol * b;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) s.acc[e] = s.acc[e] * a + oacc[e] * b;
+  s.m = M;
+}
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a) {
+  constexpr int EPL = Elem<T>::kPerLoad;
+  constexpr int LPT = D / EPL;
+  constexpr int NLD = kBlock * D * sizeof(T) / 1024;
+  constexpr size_t kSlabBytes = static_cast<size_t>(kBlock) * D * sizeof(T);
+
+  __shared__ float sm_m[kWaves][G];
+  __shared__ float sm_l[kWaves][G];
+  __shared__ float sm_acc[kWaves][G][D];
+
+  const int Hkv = a.num_kv_heads;
+  const int item = blockIdx.x / a.head_groups;
+  const int hg = blockIdx.x - item * a.head_groups;  // query heads hg*G .. hg*G+G-1
+  const int h = hg / a.kv_div;                       // KV head they read
+  if (!a.exact_grid && item >= a.hdr->total_items) return;
+  const int2 it = a.items[item];
+  const int b = it.x;
+  const int kv_len = min(a.kv_lens[b], a.max_blocks_per_seq * kBlock);  // never index past the table row
+  const int Hq = a.head_groups * G;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  const int t0 = it.y * a.chunk;
+  const int ntok = min(kv_len - t0, a.chunk);
+  if (ntok <= 0) {  // kv_len <= 0: defined result is zeros
+    for (int i = tid; i < G * D; i += kThreads) {
+      const size_t o = (static_cast<size_t>(b) * Hq + hg * G) * D + i;
+      if (a.out_bf16) reinterpret_cast<uint16_t*>(a.out)[o] = 0;
+      else reinterpret_cast<float*>(a.out)[o] = 0.f;
+    }
+    return;
+  }
+  const int ntiles = (ntok + kBlock - 1) / kBlock;
+  const bool single = kv_len <= a.chunk;
+
+  // block ids of this wave's tiles: lane i holds the id of tile wave + 4*i
+  const int my_tiles = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
+  int my_id = 0;
+  if (lane < my_tiles) {
+    my_id = a.block_table[static_cast<size_t>(b) * a.max_blocks_per_seq + t0 / kBlock + wave + kWaves * lane];
+    my_id = min(max(my_id, 0), a.num_blocks - 1);
+  }
+
+  u32x4 qr[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    qr[g] = *reinterpret_cast<const u32x4*>(a.q + ((static_cast<size_t>(b) * Hq + hg * G + g) * D +
+                                                  (lane % LPT) * EPL) * sizeof(T));
+
+  HeadState<EPL> st[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    st[g].m = kNegInf;
+    st[g].l = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) st[g].acc[e] = 0.f;
+  }
+
+  const float c = a.c;
+  const size_t head_off = static_cast<size_t>(h) * kSlabBytes;
+  const size_t block_stride = static_cast<size_t>(Hkv) * kSlabBytes;
+
+  u32x4 kA[NLD], vA[NLD], kB[NLD], vB[NLD];
+  if (my_tiles > 0) {
+    const size_t off = static_cast<size_t>(__builtin_amdgcn_readlane(my_id, 0)) * block_stride + head_off;
+    load_tile<T, D>(kA, a.k_blocks + off, lane);
+    load_tile<T, D>(vA, a.v_blocks + off, lane);
+  }
+  // only the chunk's last tile can be partial
+  const int last_tile = ntiles - 1;
+  const bool last_partial = (ntok % kBlock) != 0;
+
+  for (int i = 0; i < my_tiles; i += 2) {
+    const bool haveB = i + 1 < my_tiles;
+    if (haveB) {
+      const size_t off = static_cast<size_t>(__builtin_amdgcn_readlane(my_id, i + 1)) * block_stride + head_off;
+      load_tile<T, D>(kB, a.k_blocks + off, lane);
+      load_tile<T, D>(vB, a.v_blocks + off, lane);
+    }
+    {
+      const int tile = wave + kWaves * i;
+      if (last_partial && tile == last_tile)
+        consume_tile<T, D, G, true>(kA, vA, qr, st, c, t0 + tile * kBlock, kv_len, lane);
+      else
+        consume_tile<T, D, G, false>(kA, vA, qr, st, c, 0, 0, lane);
+    }
+    if (i + 2 < my_tiles) {
+      const size_t off = static_cast<size_t>(__builtin_amdgcn_readlane(my_id, i + 2)) * block_stride + head_off;
+      load_tile<T, D>(kA, a.k_blocks + off, lane);
+      load_tile<T, D>(vA, a.v_blocks + off, lane);
+    }
+    if (haveB) {
+      const int tile = wave + kWaves * (i + 1);
+      if (last_partial && tile == last_tile)
+        consume_tile<T, D, G, true>(kB, vB, qr, st, c, t0 + tile * kBlock, kv_len, lane);
+      else
+        consume_tile<T, D, G, false>(kB, vB, qr, st, c, 0, 0, lane);
+    }
+  }
+
+  // merge the 64/LPT token groups of the wave (lanes that hold the same dims)
+#pragma unroll
+  for (int off = LPT; off < 64; off <<= 1) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float om = __shfl_xor(st[g].m, off);
+      const float ol = __shfl_xor(st[g].l, off);
+      float oacc[EPL];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) oacc[e] = __shfl_xor(st[g].acc[e], off);
+      merge_state<EPL>(st[g], om, ol, oacc, c);
+    }
+  }
+  if (lane < LPT) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      if (lane == 0) { sm_m[wave][g] = st[g].m; sm_l[wave][g] = st[g].l; }
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sm_acc[wave][g][lane * EPL + e] = st[g].acc[e];
+    }
+  }
+  __syncthreads();
+
+  // final merge over the waves: one thread per (head, output dimension)
+  for (int idx = tid; idx < G * D; idx += kThreads) {
+    const int g = idx / D;
+    const int d = idx - g * D;
+    float M = sm_m[0][g];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w][g]);
+    float l = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float f = fast_exp2((sm_m[w][g] - M) * c);  // M is finite: the chunk has >= 1 token
+      l = fmaf(sm_l[w][g], f, l);
+      acc = fmaf(sm_acc[w][g][d], f, acc);
+    }
+    const int hq = hg * G + g;
+    if (single) {
+      const float o = acc / l;
+      const size_t oi = (static_cast<size_t>(b) * Hq + hq) * D + d;
+      if (a.out_bf16) reinterpret_cast<uint16_t*>(a.out)[oi] = f32_to_bf16_rne(o);
+      else reinterpret_cast<float*>(a.out)[oi] = o;
+    } else {
+      const size_t pi = static_cast<size_t>(item) * Hq + hq;
+      a.part_acc[pi * D + d] = acc;
+      if (d == 0) a.part_ml[pi] = make_float2(M * c, l);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ combine
+// Exact merge of a request's chunk partials (the re-association identity of
+// the online softmax): with M = max_i m_i,
+//   out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i.
+// D/4 lanes per (request, query head); each lane owns 4 output dimensions.
+template <int D>
+__global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict__ cu_chunks,
+                                                      const float2* __restrict__ part_ml,
+                                                      const float* __restrict__ part_acc,
+                                                      char* __restrict__ out, int batch, int Hq,
+                                                      int out_bf16) {
+  constexpr int LPP = D / 4;
+  const int pair = blockIdx.x * (256 / LPP) + threadIdx.x / LPP;
+  const int sub = threadIdx.x % LPP;
+  if (pair >= batch * Hq) return;
+  const int b = pair / Hq;
+  const int hq = pair - b * Hq;
+  const int first = cu_chunks[b];
+  const int n = cu_chunks[b + 1] - first;
+  if (n <= 1) return;  // finished by the attention kernel itself
+  float M = kNegInf;
+  for (int i = 0; i < n; ++i) M = fmaxf(M, part_ml[static_cast<size_t>(first + i) * Hq + hq].x);
+  float l = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int i = 0; i < n; ++i) {
+    const size_t pi = static_cast<size_t>(first + i) * Hq + hq;
+    const float2 ml = part_ml[pi];
+    const float f = fast_exp2(ml.x - M);
+    const float4 v = *reinterpret_cast<const float4*>(part_acc + pi * D + sub * 4);
+    l = fmaf(ml.y, f, l);
+    acc.x = fmaf(v.x, f, acc.x); acc.y = fmaf(v.y, f, acc.y);
+    acc.z = fmaf(v.z, f, acc.z); acc.w = fmaf(v.w, f, acc.w);
+  }
+  const float inv = 1.f / l;
+  const size_t oi = (static_cast<size_t>(b) * Hq + hq) * D + sub * 4;
+  const float o0 = acc.x * inv, o1 = acc.y * inv, o2 = acc.z * inv, o3 = acc.w * inv;
+  if (out_bf16) {
+    uint2 w;
+    w.x = f32_to_bf16_rne(o0) | (static_cast<uint32_t>(f32_to_bf16_rne(o1)) << 16);
+    w.y = f32_to_bf16_rne(o2) | (static_cast<uint32_t>(f32_to_bf16_rne(o3)) << 16);
+    *reinterpret_cast<uint2*>(out + oi * 2) = w;
+  } else {
+    *reinterpret_cast<float4*>(out + oi * 4) = make_float4(o0, o1, o2, o3);
+  }
+}
+
+// ------------------------------------------------------------------ read sweep
+// Streams the same K/V bytes with the same work split and folds them with
+// XOR: the bandwidth ceiling of this access pattern.
+template <int NLD>
+__global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab_bytes,
+                                                         uint32_t* __restrict__ checksum) {
+  const int Hkv = a.num_kv_heads;
+  const int item = blockIdx.x / Hkv;
+  const int h = blockIdx.x - item * Hkv;
+  if (!a.exact_grid && item >= a.hdr->total_items) return;
+  const int2 it = a.items[item];
+  const int b = it.x;
+  const int kv_len = min(a.kv_lens[b], a.max_blocks_per_seq * kBlock);  // never index past the table row
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int t0 = it.y * a.chunk;
+  const int ntok = min(kv_len - t0, a.chunk);
+  if (ntok <= 0) return;
+  const int ntiles = (ntok + kBlock - 1) / kBlock;
+  const int my_tiles = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
+  int my_id = 0;
+  if (lane < my_tiles) {
+    my_id = a.block_table[static_cast<size_t>(b) * a.max_blocks_per_seq + t0 / kBlock + wave + kWaves * lane];
+    my_id = min(max(my_id, 0), a.num_blocks - 1);
+  }
+  const size_t head_off = static_cast<size_t>(h) * slab_bytes;
+  const size_t block_stride = static_cast<size_t>(Hkv) * slab_bytes;
+  u32x4 x = {0, 0, 0, 0};
+  for (int i = 0; i < my_tiles; ++i) {
+    const size_t off = static_cast<size_t>(__builtin_amdgcn_readlane(my_id, i)) * block_stride + head_off;
+    const char* kp = a.k_blocks + off + lane * 16;
+    const char* vp = a.v_blocks + off + lane * 16;
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+      x ^= load128(kp + j * 1024);
+      x ^= load128(vp + j * 1024);
+    }
+  }
+  uint32_t r = x.x ^ x.y ^ x.z ^ x.w;
+  for (int off = 32; off > 0; off >>= 1) r ^= __shfl_xor(r, off);
+  if (lane == 0) atomicXor(checksum + (blockIdx.x & 255), r);
+}
+
+// ------------------------------------------------------------------ host side
+int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
+  if (p.chunk_tokens > 0) return p.chunk_tokens;
+  // aim for several workgroups per compute unit while keeping chunks long
+  // enough that the partials stay well under 1 % of the bytes moved
+  const int64_t want_items = 256 * 16;
+  int64_t c = total_tokens * p.num_kv_heads / want_items;
+  int chunk = 256;
+  while (chunk < 1024 && chunk * 2 <= c) chunk *= 2;
+  return chunk;
+}
+
+struct Checked {
+  int chunk;
+  int64_t total_tokens;  // exact when host lens are given, else worst case
+  int64_t items;         // exact or upper bound
+  bool exact;
+  bool any_split;
+  WorkspaceLayout w;
+};
+
+as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_lens_host,
+                   size_t workspace_bytes, const void* workspace, Checked* out) {
+  if (!p) return als::fail(AS_EINVAL, "%s: params is null", what);
+  if (p->batch < 1 || p->num_q_heads < 1 || p->num_kv_heads < 1 || p->num_blocks < 1 ||
+      p->max_blocks_per_seq < 1)
+    return als::fail(AS_EINVAL, "%s: batch, head counts, num_blocks and max_blocks_per_seq must be positive", what);
+  if (p->num_q_heads % p->num_kv_heads)
+    return als::fail(AS_EINVAL, "%s: num_q_heads %d is not a multiple of num_kv_heads %d", what,
+                     p->num_q_heads, p->num_kv_heads);
+  if (p->block_size != kBlock)
+    return als::fail(AS_EUNSUPPORTED, "%s: block_size %d (only 16 is built)", what, p->block_size);
+  if (p->head_dim != 64 && p->head_dim != 128)
+    return als::fail(AS_EUNSUPPORTED, "%s: head_dim %d (64 and 128 are built)", what, p->head_dim);
+  if ((p->dtype != AS_DTYPE_F32 && p->dtype != AS_DTYPE_BF16) ||
+      (p->out_dtype != AS_DTYPE_F32 && p->out_dtype != AS_DTYPE_BF16))
+    return als::fail(AS_EUNSUPPORTED, "%s: dtype %d / out_dtype %d", what, p->dtype, p->out_dtype);
+  if (!(p->scale >= 0.f) || std::isinf(p->scale))
+    return als::fail(AS_EINVAL, "%s: scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))", what);
+  if (p->chunk_tokens != 0 &&
+      (p->chunk_tokens < kBlock || p->chunk_tokens > kMaxChunk || p->chunk_tokens % kBlock))
+    return als::fail(AS_EINVAL, "%s: chunk_tokens %d must be 0 or a multiple of 16 in [16, %d]", what,
+                     p->chunk_tokens, kMaxChunk);
+  const int64_t cap = static_cast<int64_t>(p->max_blocks_per_seq) * kBlock;
+  int64_t total = 0;
+  if (kv_lens_host) {
+    for (int b = 0; b < p->batch; ++b) {
+      if (kv_lens_host[b] < 1 || kv_lens_host[b] > cap)
+        return als::fail(AS_ERANGE, "%s: kv_lens_host[%d] = %d outside [1, %lld]", what, b,
+                         kv_lens_host[b], static_cast<long long>(cap));
+      total += kv_lens_host[b];
+    }
+  } else {
+    total = cap * p->batch;
+  }
+  out->total_tokens = total;
+  out->chunk = pick_chunk(*p, total);
+  out->exact = kv_lens_host != nullptr;
+  out->any_split = true;
+  if (kv_lens_host) {
+    int64_t items = 0;
+    bool split = false;
+    for (int b = 0; b < p->batch; ++b) {
+      items += (kv_lens_host[b] + out->chunk - 1) / out->chunk;
+      split |= kv_lens_host[b] > out->chunk;
+    }
+    out->items = items;
+    out->any_split = split;
+  } else {
+    out->items = static_cast<int64_t>(p->batch) * ((cap + out->chunk - 1) / out->chunk);
+  }
+  out->w = layout_for(*p, out->items);
+  if (out->items * p->num_q_heads > 0x7FFFFFFFLL)
+    return als::fail(AS_ERANGE, "%s: %lld work items exceed the launch limit", what,
+                     static_cast<long long>(out->items * p->num_q_heads));
+  if (workspace) {
+    if (reinterpret_cast<uintptr_t>(workspace) % 256)
+      return als::fail(AS_EINVAL, "%s: workspace is not 256-byte aligned", what);
+    if (workspace_bytes < out->w.total)
+      return als::fail(AS_EWORKSPACE, "%s: workspace has %zu bytes, needs %zu", what, workspace_bytes,
+                       out->w.total);
+  }
+  return AS_OK;
+}
+
+template <typename T, int D>
+void launch_attn(int G, dim3 grid, hipStream_t s, const AttnArgs& a) {
+  switch (G) {
+    case 1: hipLaunchKernelGGL((attn_kernel<T, D, 1>), grid, dim3(kThreads), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((attn_kernel<T, D, 2>), grid, dim3(kThreads), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((attn_kernel<T, D, 4>), grid, dim3(kThreads), 0, s, a); break;
+    default: hipLaunchKernelGGL((attn_kernel<T, D, 8>), grid, dim3(kThreads), 0, s, a); break;
+  }
+}
+
+AttnArgs make_args(const as_attn_params& p, const Checked& ck, const void* q, const void* k,
+                   const void* v, const int32_t* bt, const int32_t* lens, void* out, char* ws) {
+  AttnArgs a;
+  a.q = static_cast<const char*>(q);
+  a.k_blocks = static_cast<const char*>(k);
+  a.v_blocks = static_cast<const char*>(v);
+  a.block_table = bt;
+  a.kv_lens = lens;
+  a.out = static_cast<char*>(out);
+  a.hdr = reinterpret_cast<const PlanHeader*>(ws);
+  a.items = reinterpret_cast<const int2*>(ws + ck.w.items_off);
+  a.part_ml = reinterpret_cast<float2*>(ws + ck.w.ml_off);
+  a.part_acc = reinterpret_cast<float*>(ws + ck.w.acc_off);
+  a.num_kv_heads = p.num_kv_heads;
+  a.head_groups = p.num_kv_heads;
+  a.kv_div = 1;
+  a.num_blocks = p.num_blocks;
+  a.max_blocks_per_seq = p.max_blocks_per_seq;
+  a.chunk = ck.chunk;
+  a.out_bf16 = p.out_dtype == AS_DTYPE_BF16;
+  a.exact_grid = ck.exact;
+  const float scale = p.scale > 0.f ? p.scale : 1.0f / std::sqrt(static_cast<float>(p.head_dim));
+  a.c = scale * 1.4426950408889634f;
+  return a;
+}
+
+as_status run_plan(const as_attn_params& p, const Checked& ck, const int32_t* lens, char* ws,
+                   hipStream_t s) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, lens, p.batch, ck.chunk,
+                     p.max_blocks_per_seq * kBlock,
+                     reinterpret_cast<PlanHeader*>(ws), reinterpret_cast<int32_t*>(ws + ck.w.cu_off),
+                     reinterpret_cast<int2*>(ws + ck.w.items_off), ck.w.max_items);
+  ALS_HIP_CHECK(hipGetLastError());
+  return AS_OK;
+}
+
+}  // namespace
+
+extern "C" size_t as_decode_attention_workspace(const as_attn_params* p, int64_t total_kv_tokens) {
+  Checked ck;
+  if (validate("as_decode_attention_workspace", p, nullptr, 0, nullptr, &ck) != AS_OK) return 0;
+  // Upper bound on the items of any call that fits these parameters: every
+  // request contributes ceil(L/chunk) <= L/chunk + 1 items, and the smallest
+  // chunk the library picks by itself is 256 tokens.
+  const int64_t worst = static_cast<int64_t>(p->batch) * p->max_blocks_per_seq * kBlock;
+  if (total_kv_tokens < 0 || total_kv_tokens > worst) total_kv_tokens = worst;
+  const int chunk = p->chunk_tokens > 0 ? p->chunk_tokens : 256;
+  return layout_for(*p, total_kv_tokens / chunk + p->batch).total;
+}
+
+extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, const void* v_blocks,
+                                         const int32_t* block_table, const int32_t* kv_lens,
+                                         const int32_t* kv_lens_host, void* out,
+                                         const as_attn_params* p, void* workspace,
+                                         size_t workspace_bytes, void* hip_stream) {
+  if (!q || !k_blocks || !v_blocks || !block_table || !kv_lens || !out || !workspace)
+    return als::fail(AS_EINVAL, "as_decode_attention: a required pointer is null");
+  Checked ck;
+  as_status st = validate("as_decode_attention", p, kv_lens_host, workspace_bytes, workspace, &ck);
+  if (st != AS_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  if (!(p->flags & AS_ATTN_REUSE_PLAN)) {
+    st = run_plan(*p, ck, kv_lens, ws, s);
+    if (st != AS_OK) return st;
+  }
+  AttnArgs a = make_args(*p, ck, q, k_blocks, v_blocks, block_table, kv_lens, out, ws);
+
+  // query heads handled by one workgroup: the largest of 8, 4, 2, 1 that
+  // divides the GQA group; a group that is not a power of two up to 8 is
+  // covered by several workgroups reading the same KV head
+  const int group = p->num_q_heads / p->num_kv_heads;
+  const int G = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
+  a.head_groups = p->num_q_heads / G;
+  a.kv_div = group / G;
+  const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
+  if (p->dtype == AS_DTYPE_BF16) {
+    if (p->head_dim == 128) launch_attn<bf16_t, 128>(G, grid, s, a);
+    else launch_attn<bf16_t, 64>(G, grid, s, a);
+  } else {
+    if (p->head_dim == 128) launch_attn<float, 128>(G, grid, s, a);
+    else launch_attn<float, 64>(G, grid, s, a);
+  }
+  ALS_HIP_CHECK(hipGetLastError());
+  if (ck.any_split) {
+    const int lpp = p->head_dim / 4;
+    const int pairs_per_block = 256 / lpp;
+    const int pairs = p->batch * p->num_q_heads;
+    const dim3 cgrid((pairs + pairs_per_block - 1) / pairs_per_block);
+    const int32_t* cu = reinterpret_cast<const int32_t*>(ws + ck.w.cu_off);
+    if (p->head_dim == 128)
+      hipLaunchKernelGGL(combine_kernel<128>, cgrid, dim3(256), 0, s, cu, a.part_ml, a.part_acc,
+                         a.out, p->batch, p->num_q_heads, a.out_bf16);
+    else
+      hipLaunchKernelGGL(combine_kernel<64>, cgrid, dim3(256), 0, s, cu, a.part_ml, a.part_acc,
+                         a.out, p->batch, p->num_q_heads, a.out_bf16);
+    ALS_HIP_CHECK(hipGetLastError());
+  }
+  return AS_OK;
+}
+
+extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks,
+                                      const int32_t* block_table, const int32_t* kv_lens,
+                                      const int32_t* kv_lens_host, uint32_t* checksum,
+                                      const as_attn_params* p, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  if (!k_blocks || !v_blocks || !block_table || !kv_lens || !checksum || !workspace)
+    return als::fail(AS_EINVAL, "as_kv_read_sweep: a required pointer is null");
+  Checked ck;
+  as_status st = validate("as_kv_read_sweep", p, kv_lens_host, workspace_bytes, workspace, &ck);
+  if (st != AS_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  if (!(p->flags & AS_ATTN_REUSE_PLAN)) {
+    st = run_plan(*p, ck, kv_lens, ws, s);
+    if (st != AS_OK) return st;
+  }
+  AttnArgs a = make_args(*p, ck, k_blocks, k_blocks, v_blocks, block_table, kv_lens, checksum, ws);
+  const size_t esz = p->dtype == AS_DTYPE_BF16 ? 2 : 4;
+  const size_t slab = static_cast<size_t>(kBlock) * p->head_dim * esz;
+  const dim3 grid(static_cast<unsigned>(ck.items * p->num_kv_heads));
+  switch (slab / 1024) {
+    case 2: hipLaunchKernelGGL(sweep_kernel<2>, grid, dim3(kThreads), 0, s, a, slab, checksum); break;
+    case 4: hipLaunchKernelGGL(sweep_kernel<4>, grid, dim3(kThreads), 0, s, a, slab, checksum); break;
+    default: hipLaunchKernelGGL(sweep_kernel<8>, grid, dim3(kThreads), 0, s, a, slab, checksum); break;
+  }
+  ALS_HIP_CHECK(hipGetLastError());
+  return AS_OK;
+}

@@ -1,0 +1,162 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol
+the header declares, the batcher is bit-exact against the oracle, and
+argument errors are turned into status codes before anything touches HIP."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import batcher as ob
+from paper_2605_23389_amd import binding as als
+from paper_2605_23389_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "alignedserve.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(as_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol(lib):
+    handle = lib.load()
+    declared = _declared_symbols()
+    assert len(declared) >= 12
+    for name in declared:
+        assert hasattr(handle, name), f"{name} declared in the header but not exported"
+    assert sorted(als.EXPORTS) == declared
+    assert lib.version() >= 100
+
+
+def test_aligned_batch_matches_oracle_bit_exact(lib):
+    rng = np.random.default_rng(0)
+    for trial in range(1000):
+        n = int(rng.integers(0, 300))
+        B = int(rng.integers(1, 40))
+        kind = trial % 4
+        if kind == 0:
+            lens = rng.integers(1, 70000, n)
+        elif kind == 1:
+            lens = rng.integers(1, 5, n)                       # heavy ties
+        elif kind == 2:
+            lens = np.full(n, int(rng.integers(1, 1 << 30)))   # all equal
+        else:
+            lens = rng.integers(1, np.iinfo(np.int32).max, n)  # full int32 range
+        lens = lens.astype(np.int32)
+        order, offs = lib.aligned_batch(lens, B)
+        o_order, o_offs = ob.aligned_batch(lens.tolist(), B)
+        assert order.tolist() == o_order
+        assert offs.tolist() == o_offs
+
+
+def test_aligned_batch_on_the_config_lengths(lib):
+    for cfg, B in ((2, 64), (4, 128)):
+        lens = wl.config_lengths(cfg)
+        order, offs = lib.aligned_batch(lens, B)
+        o_order, o_offs = ob.aligned_batch(lens.tolist(), B)
+        assert order.tolist() == o_order and offs.tolist() == o_offs
+    lens = wl.batcher_lengths_tiny()
+    order, offs = lib.aligned_batch(lens, 8)
+    assert (order.tolist(), offs.tolist()) == ob.aligned_batch(lens.tolist(), 8)
+    # the straggler objective: aligned beats the seeded random grouping
+    lens = wl.config_lengths(2)
+    order, offs = lib.aligned_batch(lens, 64)
+    r_order, r_offs = wl.random_grouping(len(lens), 64, seed=0)
+    assert ob.sum_of_batch_max(lens, order.tolist(), offs.tolist()) < \
+        ob.sum_of_batch_max(lens, r_order.tolist(), r_offs.tolist()) / 3
+
+
+def test_aligned_batch_errors(lib):
+    with pytest.raises(als.AlignedServeError) as e:
+        lib.aligned_batch([3, 2], 0)
+    assert e.value.status == als.AS_EINVAL
+    with pytest.raises(als.AlignedServeError) as e:
+        lib.aligned_batch([3, 0, 2], 2)
+    assert e.value.status == als.AS_EINVAL and "kv_lens[1]" in str(e.value)
+    handle = lib.load()
+    nb = C.c_int32()
+    offs = (C.c_int32 * 2)()
+    assert handle.as_aligned_batch(None, -1, 4, None, offs, C.byref(nb)) == als.AS_EINVAL
+    assert handle.as_aligned_batch(None, 3, 4, None, offs, C.byref(nb)) == als.AS_EINVAL
+    assert handle.as_aligned_batch(None, 0, 4, None, None, C.byref(nb)) == als.AS_EINVAL
+    assert handle.as_aligned_batch(None, 0, 4, None, offs, C.byref(nb)) == als.AS_OK
+    assert nb.value == 0 and offs[0] == 0
+
+
+def _params(**kw):
+    base = dict(dtype=als.DTYPE_BF16, out_dtype=als.DTYPE_BF16, batch=4, num_q_heads=8,
+                num_kv_heads=8, head_dim=128, block_size=16, num_blocks=64,
+                max_blocks_per_seq=8, scale=0.0, chunk_tokens=0, flags=0)
+    base.update(kw)
+    return als.AttnParams(**base)
+
+
+def test_decode_attention_argument_errors_before_any_gpu_work(lib):
+    handle = lib.load()
+    fake = C.c_void_p(0x1000)   # never dereferenced: every case fails validation first
+    ws_ok = C.c_void_p(0x10000)
+    lens = np.array([5, 6, 7, 8], dtype=np.int32)
+
+    def call(p, host=lens, ws=ws_ok, ws_bytes=1 << 30, q=fake):
+        hp = None if host is None else host.ctypes.data_as(C.POINTER(C.c_int32))
+        return handle.as_decode_attention(q, fake, fake, fake, fake, hp, fake, C.byref(p), ws,
+                                          ws_bytes, None)
+
+    assert call(_params(), q=None) == als.AS_EINVAL
+    assert call(_params(num_q_heads=12, num_kv_heads=8)) == als.AS_EINVAL
+    assert call(_params(batch=0)) == als.AS_EINVAL
+    assert call(_params(head_dim=96)) == als.AS_EUNSUPPORTED
+    assert call(_params(block_size=32)) == als.AS_EUNSUPPORTED
+    assert call(_params(dtype=7)) == als.AS_EUNSUPPORTED
+    assert call(_params(chunk_tokens=24)) == als.AS_EINVAL
+    assert call(_params(chunk_tokens=8192)) == als.AS_EINVAL
+    assert call(_params(scale=-1.0)) == als.AS_EINVAL
+    assert call(_params(), host=np.array([5, 0, 7, 8], dtype=np.int32)) == als.AS_ERANGE
+    assert call(_params(), host=np.array([5, 129, 7, 8], dtype=np.int32)) == als.AS_ERANGE
+    assert "kv_lens_host[1]" in handle.as_last_error().decode()
+    assert call(_params(), ws_bytes=16) == als.AS_EWORKSPACE
+    assert call(_params(), ws=C.c_void_p(0x10010)) == als.AS_EINVAL
+
+
+def test_workspace_size_query(lib):
+    p = _params()
+    worst = lib.decode_attention_workspace(p, -1)
+    assert worst > 0 and worst % 256 == 0
+    small = lib.decode_attention_workspace(p, 26)
+    assert 0 < small <= worst
+    assert lib.decode_attention_workspace(_params(head_dim=100), -1) == 0
+    # monotone in the token count
+    p2 = _params(batch=64, max_blocks_per_seq=2048, num_blocks=1 << 20)
+    sizes = [lib.decode_attention_workspace(p2, t) for t in (1000, 100000, 1000000, -1)]
+    assert sizes == sorted(sizes)
+
+
+def test_stage_kv_argument_errors(lib):
+    handle = lib.load()
+    fake = C.c_void_p(0x1000)
+    src = (C.c_int64 * 2)(0, 9)
+    dst = (C.c_int32 * 2)(0, 1)
+    assert handle.as_stage_kv(fake, fake, src, 4, fake, fake, dst, 4, 2, 4096, None) == als.AS_ERANGE
+    assert "host block id [1]" in handle.as_last_error().decode()
+    src = (C.c_int64 * 2)(0, 1)
+    dst = (C.c_int32 * 2)(0, 7)
+    assert handle.as_stage_kv(fake, fake, src, 4, fake, fake, dst, 4, 2, 4096, None) == als.AS_ERANGE
+    assert handle.as_stage_kv(fake, fake, src, 4, fake, fake, dst, 8, -1, 4096, None) == als.AS_EINVAL
+    assert handle.as_stage_kv(fake, fake, src, 4, fake, fake, dst, 8, 2, 100, None) == als.AS_EINVAL
+    assert handle.as_stage_kv(None, fake, src, 4, fake, fake, dst, 8, 2, 4096, None) == als.AS_EINVAL
+    assert handle.as_stage_kv(fake, None, src, 4, fake, fake, dst, 8, 2, 4096, None) == als.AS_EINVAL
+    assert handle.as_stage_kv(fake, fake, src, 4, fake, fake, dst, 8, 0, 4096, None) == als.AS_OK
+    assert handle.as_unstage_kv(fake, fake, src, 4, fake, fake, dst, 8, -3, 4096, None) == als.AS_EINVAL
+
+
+def test_pipeline_argument_errors(lib):
+    handle = lib.load()
+    assert handle.as_pipeline_create(None, 2) == als.AS_EINVAL
+    h = C.c_void_p()
+    assert handle.as_pipeline_create(C.byref(h), 0) == als.AS_EINVAL
+    assert handle.as_pipeline_create(C.byref(h), 9) == als.AS_EINVAL
+    assert handle.as_pipeline_begin_stage(None, 0) == als.AS_EINVAL
+    assert handle.as_pipeline_destroy(None) == als.AS_EINVAL
