@@ -57,6 +57,10 @@ def load() -> C.CDLL:
         raise RuntimeError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2605_23389_amd.build` "
             "(hipcc, gfx950). There is no CPU or PyTorch fallback for the hot path.")
+    # PyTorch ships its own HIP runtime (same soname as the system one).  It
+    # must be the one already mapped when this library is loaded, otherwise the
+    # process ends up with two runtimes and the second one sees no device.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     i32p, i64p, vp = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.c_void_p
     lib.as_version.restype = C.c_int32

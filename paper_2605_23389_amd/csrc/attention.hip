@@ -43,6 +43,7 @@ constexpr int kMaxChunk = 64 * kWaves * kBlock;  // one block id per lane per wa
 constexpr float kNegInf = -__builtin_huge_valf();
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
@@ -164,11 +165,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 // dot of the EPL elements a lane holds of one key row with its slice of q
 template <typename T> struct Dot;
 template <> struct Dot<float> {
-  __device__ static __forceinline__ float run(const u32x4& k, const u32x4& q) {
-    float s = __builtin_bit_cast(float, k.x) * __builtin_bit_cast(float, q.x);
-    s = fmaf(__builtin_bit_cast(float, k.y), __builtin_bit_cast(float, q.y), s);
-    s = fmaf(__builtin_bit_cast(float, k.z), __builtin_bit_cast(float, q.z), s);
-    s = fmaf(__builtin_bit_cast(float, k.w), __builtin_bit_cast(float, q.w), s);
+  // Reinterpret the whole vector, then index: a bit_cast applied to a single
+  // element of the loaded vector makes this compiler read element 0 each time.
+  __device__ static __forceinline__ float run(const u32x4& ku, const u32x4& qu) {
+    const f32x4 k = __builtin_bit_cast(f32x4, ku);
+    const f32x4 q = __builtin_bit_cast(f32x4, qu);
+    float s = k.x * q.x;
+    s = fmaf(k.y, q.y, s);
+    s = fmaf(k.z, q.z, s);
+    s = fmaf(k.w, q.w, s);
     return s;
   }
 };
@@ -192,9 +197,9 @@ template <> struct Dot<bf16_t> {
 // widen the EPL elements of one loaded 128-bit word to fp32
 template <typename T> struct Widen;
 template <> struct Widen<float> {
-  __device__ static __forceinline__ void run(const u32x4& v, float (&o)[4]) {
-    o[0] = __builtin_bit_cast(float, v.x); o[1] = __builtin_bit_cast(float, v.y);
-    o[2] = __builtin_bit_cast(float, v.z); o[3] = __builtin_bit_cast(float, v.w);
+  __device__ static __forceinline__ void run(const u32x4& vu, float (&o)[4]) {
+    const f32x4 v = __builtin_bit_cast(f32x4, vu);
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
   }
 };
 template <> struct Widen<bf16_t> {
