@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--skip-extra", action="store_true",
                     help="only the headline pass (used for profiling runs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 2 GiB device-to-device copies (a kernel of known "
+                         "traffic, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
@@ -110,6 +113,14 @@ def main():
     def step_random():
         for b in batches_r:
             attend(b)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 31, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------- headline: K timed steps over the aligned batches
     for _ in range(args.warmup):
