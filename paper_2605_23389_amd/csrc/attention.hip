@@ -44,6 +44,9 @@ constexpr float kNegInf = -__builtin_huge_valf();
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
@@ -481,6 +484,271 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a) {
   }
 }
 
+// ------------------------------------------------------------------ MFMA path
+// Grouped-query attention (G query heads share one KV head), bf16, D = 128.
+// With G >= 4 the vector-ALU kernel above is bound by its own arithmetic (each
+// K/V element is used G times), so the two contractions move to the matrix
+// cores; the K/V stream, the work split and the merge stay as they are.
+//
+//   S^T[token][head] = K_tile[16 x 128] . Q^T[128 x 16]      4 x mfma 16x16x32
+//   O^T[dim][head]  += V_tile^T[128 x 16] . P^T[16 x 16]     8 x mfma 16x16x16
+//
+// Operand layouts (lane l, c = l % 16, r = l / 16):
+//  * A operand of a 16x16x32 MFMA wants lane l to hold 8 consecutive
+//    contraction values of matrix row c.  The coalesced global load gives a
+//    lane a token picked by r and a 16-byte dimension chunk picked by c -- the
+//    transpose.  K therefore passes through a per-wave LDS tile (rows padded
+//    to 272 B: conflict-free 128-bit writes and reads), written in load layout
+//    and read back in operand layout.  Token t is put in LDS row
+//    4*(t%4) + t/4, so that result register i of lane l (matrix row 4r+i)
+//    belongs to token 4i+r: the token whose V elements the same lane loaded.
+//  * B operand = Q^T: lane l holds q[head c][dims of contraction slots]; heads
+//    past G are zero columns.
+//  * The result S^T has the head on c and tokens on (r, i): a lane owns ONE
+//    head, so the online softmax costs the same for any G <= 16.
+//  * P^T (B operand of the second MFMA) is exactly what the lane computed:
+//    probabilities of its 4 tokens for head c, rounded to bf16.
+//  * V needs no LDS: the lane's four loads hold, for each of its 8 dimensions,
+//    the 4 tokens (4i+r) -- the A operand (row = dimension 8c+e, 4 contraction
+//    values) once the 16-bit halves are gathered with v_perm.  Output register
+//    i of accumulator e is dimension 32r+8i+e of head c: the lane that owns a
+//    head's softmax state also owns that head's outputs, so rescaling is
+//    lane-local.
+// The sum l is accumulated from the bf16-rounded probabilities, so numerator
+// and denominator use the same weights.
+constexpr int kLdsRow = 272;                    // 256 B of a K row + 16 B pad
+constexpr int kLdsKTile = kBlock * kLdsRow;     // per wave
+constexpr int kMfmaHeads = 16;
+
+template <bool MASKED>
+__device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr)[4],
+                                          const bf16x8_t (&qb)[4], char* lds, f32x4 (&acc)[8],
+                                          float& m_run, float& l_run, float c, int first_token,
+                                          int kv_len, int lane) {
+  const int col = lane & 15;
+  const int rg = lane >> 4;
+  // K: load layout -> LDS (row 4*rg+i holds token 4*i+rg), then operand layout
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    *reinterpret_cast<u32x4*>(lds + (4 * rg + i) * kLdsRow + col * 16) = kr[i];
+  __builtin_amdgcn_wave_barrier();
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const u32x4 ku = *reinterpret_cast<const u32x4*>(lds + col * kLdsRow + (4 * j + rg) * 16);
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ku), qb[j], s, 0, 0, 0);
+  }
+  __builtin_amdgcn_wave_barrier();
+
+  float sv[4] = {s.x, s.y, s.z, s.w};
+  bool valid[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    valid[i] = !MASKED || (first_token + 4 * i + rg < kv_len);
+    if (MASKED) sv[i] = valid[i] ? sv[i] : kNegInf;
+  }
+  float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));           // max over the tile's 16 tokens, per head
+  const float m_new = fmaxf(m_run, mx);          // finite: a tile has at least one valid token
+  const float alpha = fast_exp2((m_run - m_new) * c);
+  const float nref = -m_new * c;
+  float p[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    p[i] = fast_exp2(fmaf(sv[i], c, nref));
+    if (MASKED) p[i] = valid[i] ? p[i] : 0.f;
+  }
+  const f32x2 p01 = {p[0], p[1]}, p23 = {p[2], p[3]};
+  const bf16x2_t b01 = __builtin_convertvector(p01, bf16x2_t);
+  const bf16x2_t b23 = __builtin_convertvector(p23, bf16x2_t);
+  const uint32_t w01 = __builtin_bit_cast(uint32_t, b01);
+  const uint32_t w23 = __builtin_bit_cast(uint32_t, b23);
+  const float psum = (bf16_lo(w01) + bf16_hi(w01)) + (bf16_lo(w23) + bf16_hi(w23));
+  l_run = fmaf(l_run, alpha, psum);
+  m_run = m_new;
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+  }
+  const u32x2 pw = {w01, w23};
+  const s16x4 pB = __builtin_bit_cast(s16x4, pw);
+
+  // V: gather the 16-bit halves of the 4 tokens for each of the lane's 8 dims
+  u32x4 v0 = vr[0], v1 = vr[1], v2 = vr[2], v3 = vr[3];
+  if (MASKED) {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    v0 = valid[0] ? v0 : zero; v1 = valid[1] ? v1 : zero;
+    v2 = valid[2] ? v2 : zero; v3 = valid[3] ? v3 : zero;
+  }
+  const uint32_t a0[4] = {v0.x, v0.y, v0.z, v0.w};
+  const uint32_t a1[4] = {v1.x, v1.y, v1.z, v1.w};
+  const uint32_t a2[4] = {v2.x, v2.y, v2.z, v2.w};
+  const uint32_t a3[4] = {v3.x, v3.y, v3.z, v3.w};
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const u32x2 lo = {__builtin_amdgcn_perm(a1[w], a0[w], 0x05040100u),
+                      __builtin_amdgcn_perm(a3[w], a2[w], 0x05040100u)};
+    const u32x2 hi = {__builtin_amdgcn_perm(a1[w], a0[w], 0x07060302u),
+                      __builtin_amdgcn_perm(a3[w], a2[w], 0x07060302u)};
+    acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, lo), pB, acc[2 * w], 0, 0, 0);
+    acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, hi), pB, acc[2 * w + 1], 0, 0, 0);
+  }
+}
+
+// G = query heads per workgroup (<= 16), D = 128, bf16.
+__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G) {
+  constexpr int D = 128;
+  constexpr size_t kSlabBytes = static_cast<size_t>(kBlock) * D * 2;
+  // the K transpose tiles (loop) and the cross-wave merge buffers (epilogue)
+  // share one allocation; a barrier separates the two uses
+  constexpr int kMergeBytes = kWaves * kMfmaHeads * D * 4;
+  __shared__ __attribute__((aligned(16))) char smem[kMergeBytes];
+  __shared__ float sm_m[kWaves][kMfmaHeads];
+  __shared__ float sm_l[kWaves][kMfmaHeads];
+  static_assert(kWaves * kLdsKTile <= kMergeBytes, "K tiles must fit the shared buffer");
+
+  const int Hkv = a.num_kv_heads;
+  const int item = blockIdx.x / a.head_groups;
+  const int hg = blockIdx.x - item * a.head_groups;
+  const int h = hg / a.kv_div;
+  if (!a.exact_grid && item >= a.hdr->total_items) return;
+  const int2 it = a.items[item];
+  const int b = it.x;
+  const int kv_len = min(a.kv_lens[b], a.max_blocks_per_seq * kBlock);
+  const int Hq = a.head_groups * G;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = lane & 15;
+  const int rg = lane >> 4;
+
+  const int t0 = it.y * a.chunk;
+  const int ntok = min(kv_len - t0, a.chunk);
+  if (ntok <= 0) {
+    for (int i = tid; i < G * D; i += kThreads) {
+      const size_t o = (static_cast<size_t>(b) * Hq + hg * G) * D + i;
+      if (a.out_bf16) reinterpret_cast<uint16_t*>(a.out)[o] = 0;
+      else reinterpret_cast<float*>(a.out)[o] = 0.f;
+    }
+    return;
+  }
+  const int ntiles = (ntok + kBlock - 1) / kBlock;
+  const bool single = kv_len <= a.chunk;
+  const int my_tiles = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
+  int my_id = 0;
+  if (lane < my_tiles) {
+    my_id = a.block_table[static_cast<size_t>(b) * a.max_blocks_per_seq + t0 / kBlock + wave + kWaves * lane];
+    my_id = min(max(my_id, 0), a.num_blocks - 1);
+  }
+
+  // Q^T operand: head `col`, dims 8*(4j+rg) .. +8 for MFMA j; zero past G
+  bf16x8_t qb[4];
+  {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    const char* qrow = a.q + (static_cast<size_t>(b) * Hq + hg * G + (col < G ? col : 0)) * D * 2;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x4 w = *reinterpret_cast<const u32x4*>(qrow + (4 * j + rg) * 16);
+      w = col < G ? w : zero;
+      qb[j] = __builtin_bit_cast(bf16x8_t, w);
+    }
+  }
+
+  f32x4 acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = kNegInf, l_run = 0.f;
+  const float c = a.c;
+  char* lds = smem + wave * kLdsKTile;
+  const size_t head_off = static_cast<size_t>(h) * kSlabBytes;
+  const size_t block_stride = static_cast<size_t>(Hkv) * kSlabBytes;
+
+  u32x4 kA[4], vA[4], kB[4], vB[4];
+  auto tile_off = [&](int i) {
+    return static_cast<size_t>(__builtin_amdgcn_readlane(my_id, i)) * block_stride + head_off;
+  };
+  if (my_tiles > 0) {
+    const size_t off = tile_off(0);
+    load_tile<bf16_t, D>(kA, a.k_blocks + off, lane);
+    load_tile<bf16_t, D>(vA, a.v_blocks + off, lane);
+  }
+  // Only the chunk's last tile can be partial.  The hot loop takes pairs of
+  // full tiles with the unmasked code; at most two tiles are left for the
+  // masked code after it.
+  const bool owns_partial = (ntok % kBlock) != 0 && ((ntiles - 1) % kWaves) == wave;
+  const int full_tiles = my_tiles - (owns_partial ? 1 : 0);
+  int i = 0;
+  for (; i + 2 <= full_tiles; i += 2) {
+    {
+      const size_t off = tile_off(i + 1);
+      load_tile<bf16_t, D>(kB, a.k_blocks + off, lane);
+      load_tile<bf16_t, D>(vB, a.v_blocks + off, lane);
+    }
+    mfma_tile<false>(kA, vA, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
+    if (i + 2 < my_tiles) {
+      const size_t off = tile_off(i + 2);
+      load_tile<bf16_t, D>(kA, a.k_blocks + off, lane);
+      load_tile<bf16_t, D>(vA, a.v_blocks + off, lane);
+    }
+    mfma_tile<false>(kB, vB, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
+  }
+  if (i < my_tiles) {
+    const bool haveB = i + 1 < my_tiles;
+    if (haveB) {
+      const size_t off = tile_off(i + 1);
+      load_tile<bf16_t, D>(kB, a.k_blocks + off, lane);
+      load_tile<bf16_t, D>(vB, a.v_blocks + off, lane);
+    }
+    mfma_tile<true>(kA, vA, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * i) * kBlock, kv_len, lane);
+    if (haveB)
+      mfma_tile<true>(kB, vB, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * (i + 1)) * kBlock, kv_len, lane);
+  }
+
+  // each row group summed its own 4 tokens per tile; m is already common
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+
+  __syncthreads();  // every wave is done with its K tile: the buffer becomes merge space
+  float* sm_o = reinterpret_cast<float*>(smem);  // [wave][head][D]
+  if (col < G) {
+    if (rg == 0) { sm_m[wave][col] = m_run; sm_l[wave][col] = l_run; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float v[4] = {acc[e].x, acc[e].y, acc[e].z, acc[e].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sm_o[(wave * kMfmaHeads + col) * D + 32 * rg + 8 * i + e] = v[i];
+    }
+  }
+  __syncthreads();
+
+  for (int idx = tid; idx < G * D; idx += kThreads) {
+    const int g = idx / D;
+    const int d = idx - g * D;
+    float M = sm_m[0][g];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w][g]);
+    float l = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float f = fast_exp2((sm_m[w][g] - M) * c);
+      l = fmaf(sm_l[w][g], f, l);
+      o = fmaf(sm_o[(w * kMfmaHeads + g) * D + d], f, o);
+    }
+    const int hq = hg * G + g;
+    if (single) {
+      const float r = o / l;
+      const size_t oi = (static_cast<size_t>(b) * Hq + hq) * D + d;
+      if (a.out_bf16) reinterpret_cast<uint16_t*>(a.out)[oi] = f32_to_bf16_rne(r);
+      else reinterpret_cast<float*>(a.out)[oi] = r;
+    } else {
+      const size_t pi = static_cast<size_t>(item) * Hq + hq;
+      a.part_acc[pi * D + d] = o;
+      if (d == 0) a.part_ml[pi] = make_float2(M * c, l);
+    }
+  }
+}
+
 // ------------------------------------------------------------------ combine
 // Exact merge of a request's chunk partials (the re-association identity of
 // the online softmax): with M = max_i m_i,
@@ -734,20 +1002,36 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
   }
   AttnArgs a = make_args(*p, ck, q, k_blocks, v_blocks, block_table, kv_lens, out, ws);
 
-  // query heads handled by one workgroup: the largest of 8, 4, 2, 1 that
-  // divides the GQA group; a group that is not a power of two up to 8 is
-  // covered by several workgroups reading the same KV head
   const int group = p->num_q_heads / p->num_kv_heads;
-  const int G = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
-  a.head_groups = p->num_q_heads / G;
-  a.kv_div = group / G;
-  const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
-  if (p->dtype == AS_DTYPE_BF16) {
-    if (p->head_dim == 128) launch_attn<bf16_t, 128>(G, grid, s, a);
-    else launch_attn<bf16_t, 64>(G, grid, s, a);
+  // Matrix-core path: bf16, D = 128, grouped-query shapes where the vector-ALU
+  // kernel is bound by its own arithmetic.  One workgroup takes up to 16 heads
+  // of a group; wider groups are cut into 16s or 8s.
+  int mfma_heads = 0;
+  if (p->dtype == AS_DTYPE_BF16 && p->head_dim == 128 && group >= 4 && !(p->flags & AS_ATTN_NO_MFMA)) {
+    if (group <= 16) mfma_heads = group;
+    else if (group % 16 == 0) mfma_heads = 16;
+    else if (group % 8 == 0) mfma_heads = 8;
+  }
+  if (mfma_heads) {
+    a.head_groups = p->num_q_heads / mfma_heads;
+    a.kv_div = group / mfma_heads;
+    const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
+    hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(kThreads), 0, s, a, mfma_heads);
   } else {
-    if (p->head_dim == 128) launch_attn<float, 128>(G, grid, s, a);
-    else launch_attn<float, 64>(G, grid, s, a);
+    // query heads handled by one workgroup: the largest of 8, 4, 2, 1 that
+    // divides the GQA group; a group that is not a power of two up to 8 is
+    // covered by several workgroups reading the same KV head
+    const int G = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
+    a.head_groups = p->num_q_heads / G;
+    a.kv_div = group / G;
+    const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
+    if (p->dtype == AS_DTYPE_BF16) {
+      if (p->head_dim == 128) launch_attn<bf16_t, 128>(G, grid, s, a);
+      else launch_attn<bf16_t, 64>(G, grid, s, a);
+    } else {
+      if (p->head_dim == 128) launch_attn<float, 128>(G, grid, s, a);
+      else launch_attn<float, 64>(G, grid, s, a);
+    }
   }
   ALS_HIP_CHECK(hipGetLastError());
   if (ck.any_split) {

@@ -54,13 +54,19 @@ def test_result_independent_of_split(lib, dtype):
     pb = wl.make_paged_batch(lens, 8, 2, 128, dtype=dtype, seed=5, poison="nan", spare_blocks=1)
     ref = oracle_out(pb)
     dev = to_device(pb)
-    outs = []
-    for chunk in (16, 48, 112, 256, 1024, 4096, 0):
-        got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=chunk, dev=dev)
-        assert np.abs(got - ref).max() <= TOL[dtype]
-        outs.append(got)
-    spread = max(np.abs(o - outs[0]).max() for o in outs)
-    assert spread <= 2e-6 if dtype == "fp32" else spread <= 1e-5
+    from paper_2605_23389_amd import binding as als
+    # the vector-ALU kernel keeps probabilities in fp32: the split only changes
+    # the summation order.  The matrix-core kernel (bf16, group of 4 here)
+    # rounds probabilities to bf16 relative to each chunk's own maximum, so
+    # different splits differ by that rounding (still inside the tolerance).
+    for flags, bound in ((als.ATTN_NO_MFMA, 2e-6 if dtype == "fp32" else 1e-5), (0, 5e-3)):
+        outs = []
+        for chunk in (16, 48, 112, 256, 1024, 4096, 0):
+            got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=chunk, dev=dev, flags=flags)
+            assert np.abs(got - ref).max() <= TOL[dtype]
+            outs.append(got)
+        spread = max(np.abs(o - outs[0]).max() for o in outs)
+        assert spread <= bound, f"spread {spread:.3e} (flags {flags})"
 
 
 def test_without_host_lens_and_plan_reuse(lib):
@@ -171,3 +177,40 @@ def test_read_sweep_checksum_is_xor_of_referenced_blocks(lib):
             want ^= np.bitwise_xor.reduce(pb.k_blocks[blk].reshape(-1).view(np.uint32))
             want ^= np.bitwise_xor.reduce(pb.v_blocks[blk].reshape(-1).view(np.uint32))
     assert got == want
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (8, 1), (16, 1), (32, 2), (32, 1), (24, 1), (5, 1), (12, 1)])
+def test_matrix_core_path_matches_oracle_and_vector_path(lib, Hq, Hkv):
+    """bf16, D=128 grouped-query shapes: the MFMA kernel (default for groups
+    >= 4) and the vector-ALU kernel (forced) both meet the bf16 tolerance."""
+    from paper_2605_23389_amd import binding as als
+    lens = np.array([1, 3, 16, 17, 31, 64, 65, 100, 255, 256, 257, 300, 513, 1000, 1037], dtype=np.int32)
+    for poison in ("nan", "big"):
+        pb = wl.make_paged_batch(lens, Hq, Hkv, 128, dtype="bf16", seed=Hq * 3 + Hkv, spare_blocks=2,
+                                 poison=poison, extra_table_cols=2)
+        ref = oracle_out(pb)
+        dev = to_device(pb)
+        for chunk in (0, 64, 512):
+            got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=chunk, dev=dev)
+            assert np.isfinite(got).all()
+            assert np.abs(got - ref).max() <= TOL["bf16"]
+        valu = run_attention(lib, pb, out_dtype="fp32", dev=dev, flags=als.ATTN_NO_MFMA)
+        assert np.abs(valu - ref).max() <= TOL["bf16"]
+
+
+def test_matrix_core_path_one_hot_and_mean_limits(lib):
+    """Single-token requests return v exactly and identical keys give the mean
+    of V also through the MFMA kernel (bf16 probabilities)."""
+    pb = wl.make_paged_batch(np.ones(2, dtype=np.int32), 8, 1, 128, dtype="bf16", seed=12, poison="nan")
+    got = run_attention(lib, pb, out_dtype="fp32")
+    v = pb.as_float("v_blocks").astype(np.float64)
+    for b in range(2):
+        for h in range(8):
+            assert np.array_equal(got[b, h], v[pb.block_table[b, 0], 0, 0])
+    pb = wl.make_paged_batch(np.array([128], dtype=np.int32), 8, 1, 128, dtype="bf16", seed=13)
+    k0 = pb.k_blocks[pb.block_table[0, 0], :, 0, :].copy()
+    for j in range(8):
+        pb.k_blocks[pb.block_table[0, j]] = k0[:, None, :]
+    got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=64)
+    rows = np.concatenate([pb.as_float("v_blocks")[pb.block_table[0, j]] for j in range(8)], axis=1)
+    assert np.abs(got[0] - rows.astype(np.float64).mean(axis=1)).max() <= 1e-5
