@@ -59,7 +59,7 @@ template <> struct Elem<bf16_t> { static constexpr int kPerLoad = 8; };
 // ------------------------------------------------------------------ workspace
 // [0,256)            PlanHeader
 // cu_chunks          int32[batch + 1]   first item of each request
-// items              int2[max_items]    (request, chunk index)
+// items              int4[max_items]    (request, chunk index, kv_len, 0)
 // part_ml            float2[max_items * H_q]   (running max in log2 units, sum)
 // part_acc           float[max_items * H_q * D]
 struct PlanHeader {
@@ -79,7 +79,7 @@ WorkspaceLayout layout_for(const as_attn_params& p, int64_t max_items) {
   w.max_items = max_items;
   w.cu_off = sizeof(PlanHeader);
   w.items_off = align256(w.cu_off + sizeof(int32_t) * (static_cast<size_t>(p.batch) + 1));
-  w.ml_off = align256(w.items_off + sizeof(int2) * static_cast<size_t>(w.max_items));
+  w.ml_off = align256(w.items_off + sizeof(int4) * static_cast<size_t>(w.max_items));
   w.acc_off = align256(w.ml_off + sizeof(float2) * static_cast<size_t>(w.max_items) * p.num_q_heads);
   w.total = align256(w.acc_off + sizeof(float) * static_cast<size_t>(w.max_items) * p.num_q_heads *
                                      p.head_dim);
@@ -93,7 +93,7 @@ WorkspaceLayout layout_for(const as_attn_params& p, int64_t max_items) {
 __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ kv_lens, int batch,
                                                    int chunk, int max_len, PlanHeader* __restrict__ hdr,
                                                    int32_t* __restrict__ cu_chunks,
-                                                   int2* __restrict__ items, int64_t max_items) {
+                                                   int4* __restrict__ items, int64_t max_items) {
   __shared__ int32_t part[256];
   const int tid = threadIdx.x;
   const int per = (batch + 255) / 256;
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ k
       const int mid = (a + z) >> 1;
       if (cu_chunks[mid] <= i) a = mid; else z = mid;
     }
-    items[i] = make_int2(a, static_cast<int>(i - cu_chunks[a]));
+    items[i] = make_int4(a, static_cast<int>(i - cu_chunks[a]), min(kv_lens[a], max_len), 0);
   }
 }
 
@@ -224,7 +224,7 @@ struct AttnArgs {
   const int32_t* kv_lens;
   char* out;
   const PlanHeader* hdr;
-  const int2* items;
+  const int4* items;
   float2* part_ml;
   float* part_acc;
   int32_t num_kv_heads;
@@ -234,7 +234,8 @@ struct AttnArgs {
   int32_t max_blocks_per_seq;
   int32_t chunk;
   int32_t out_bf16;
-  int32_t exact_grid;  // grid == total_items * num_kv_heads exactly
+  int32_t exact_grid;  // grid == total_items * head_groups exactly
+  int32_t direct;      // every request is one chunk: item i is request i, no item table
   float c;             // scale * log2(e)
 };
 
@@ -347,9 +348,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a) {
   const int hg = blockIdx.x - item * a.head_groups;  // query heads hg*G .. hg*G+G-1
   const int h = hg / a.kv_div;                       // KV head they read
   if (!a.exact_grid && item >= a.hdr->total_items) return;
-  const int2 it = a.items[item];
+  int4 it;
+  if (a.direct) it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
+  else it = a.items[item];
   const int b = it.x;
-  const int kv_len = min(a.kv_lens[b], a.max_blocks_per_seq * kBlock);  // never index past the table row
+  const int kv_len = it.z;  // already cut to the block_table row
   const int Hq = a.head_groups * G;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -613,9 +616,11 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G) 
   const int hg = blockIdx.x - item * a.head_groups;
   const int h = hg / a.kv_div;
   if (!a.exact_grid && item >= a.hdr->total_items) return;
-  const int2 it = a.items[item];
+  int4 it;
+  if (a.direct) it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
+  else it = a.items[item];
   const int b = it.x;
-  const int kv_len = min(a.kv_lens[b], a.max_blocks_per_seq * kBlock);
+  const int kv_len = it.z;  // already cut to the block_table row
   const int Hq = a.head_groups * G;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -805,9 +810,11 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab
   const int item = blockIdx.x / Hkv;
   const int h = blockIdx.x - item * Hkv;
   if (!a.exact_grid && item >= a.hdr->total_items) return;
-  const int2 it = a.items[item];
+  int4 it;
+  if (a.direct) it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
+  else it = a.items[item];
   const int b = it.x;
-  const int kv_len = min(a.kv_lens[b], a.max_blocks_per_seq * kBlock);  // never index past the table row
+  const int kv_len = it.z;  // already cut to the block_table row
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -824,14 +831,27 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab
   const size_t head_off = static_cast<size_t>(h) * slab_bytes;
   const size_t block_stride = static_cast<size_t>(Hkv) * slab_bytes;
   u32x4 x = {0, 0, 0, 0};
-  for (int i = 0; i < my_tiles; ++i) {
+  // same software pipeline as the attention kernel: the K and V slabs of the
+  // next tile are requested before the current tile is folded
+  u32x4 rA[2 * NLD], rB[2 * NLD];
+  auto issue = [&](u32x4 (&r)[2 * NLD], int i) {
     const size_t off = static_cast<size_t>(__builtin_amdgcn_readlane(my_id, i)) * block_stride + head_off;
-    const char* kp = a.k_blocks + off + lane * 16;
-    const char* vp = a.v_blocks + off + lane * 16;
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
-      x ^= load128(kp + j * 1024);
-      x ^= load128(vp + j * 1024);
+      r[j] = load128(a.k_blocks + off + lane * 16 + j * 1024);
+      r[NLD + j] = load128(a.v_blocks + off + lane * 16 + j * 1024);
+    }
+  };
+  if (my_tiles > 0) issue(rA, 0);
+  for (int i = 0; i < my_tiles; i += 2) {
+    const bool haveB = i + 1 < my_tiles;
+    if (haveB) issue(rB, i + 1);
+#pragma unroll
+    for (int j = 0; j < 2 * NLD; ++j) x ^= rA[j];
+    if (i + 2 < my_tiles) issue(rA, i + 2);
+    if (haveB) {
+#pragma unroll
+      for (int j = 0; j < 2 * NLD; ++j) x ^= rB[j];
     }
   }
   uint32_t r = x.x ^ x.y ^ x.z ^ x.w;
@@ -842,12 +862,15 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab
 // ------------------------------------------------------------------ host side
 int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
   if (p.chunk_tokens > 0) return p.chunk_tokens;
-  // aim for several workgroups per compute unit while keeping chunks long
-  // enough that the partials stay well under 1 % of the bytes moved
+  // Long chunks amortise a workgroup's start-up (dependent loads of the item,
+  // the block ids and the first tile) and its merge; short chunks balance the
+  // tail of the launch.  Measured on MI355X the longest chunk wins as long as
+  // the launch keeps a few thousand workgroups, so: the largest power of two
+  // in [256, 4096] that still leaves about 16 workgroups per compute unit.
   const int64_t want_items = 256 * 16;
-  int64_t c = total_tokens * p.num_kv_heads / want_items;
+  const int64_t c = total_tokens * p.num_kv_heads / want_items;
   int chunk = 256;
-  while (chunk < 1024 && chunk * 2 <= c) chunk *= 2;
+  while (chunk < kMaxChunk && chunk * 2 <= c) chunk *= 2;
   return chunk;
 }
 
@@ -896,6 +919,13 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
   }
   out->total_tokens = total;
   out->chunk = pick_chunk(*p, total);
+  if (kv_lens_host && p->chunk_tokens == 0) {
+    // a batch of short requests: one chunk per request, so that neither the
+    // plan nor the combine kernel is needed
+    int max_len = 0;
+    for (int b = 0; b < p->batch; ++b) max_len = kv_lens_host[b] > max_len ? kv_lens_host[b] : max_len;
+    if (max_len <= 1024 && out->chunk < max_len) out->chunk = (max_len + kBlock - 1) / kBlock * kBlock;
+  }
   out->exact = kv_lens_host != nullptr;
   out->any_split = true;
   if (kv_lens_host) {
@@ -944,7 +974,7 @@ AttnArgs make_args(const as_attn_params& p, const Checked& ck, const void* q, co
   a.kv_lens = lens;
   a.out = static_cast<char*>(out);
   a.hdr = reinterpret_cast<const PlanHeader*>(ws);
-  a.items = reinterpret_cast<const int2*>(ws + ck.w.items_off);
+  a.items = reinterpret_cast<const int4*>(ws + ck.w.items_off);
   a.part_ml = reinterpret_cast<float2*>(ws + ck.w.ml_off);
   a.part_acc = reinterpret_cast<float*>(ws + ck.w.acc_off);
   a.num_kv_heads = p.num_kv_heads;
@@ -955,6 +985,7 @@ AttnArgs make_args(const as_attn_params& p, const Checked& ck, const void* q, co
   a.chunk = ck.chunk;
   a.out_bf16 = p.out_dtype == AS_DTYPE_BF16;
   a.exact_grid = ck.exact;
+  a.direct = ck.exact && !ck.any_split;
   const float scale = p.scale > 0.f ? p.scale : 1.0f / std::sqrt(static_cast<float>(p.head_dim));
   a.c = scale * 1.4426950408889634f;
   return a;
@@ -965,7 +996,7 @@ as_status run_plan(const as_attn_params& p, const Checked& ck, const int32_t* le
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, lens, p.batch, ck.chunk,
                      p.max_blocks_per_seq * kBlock,
                      reinterpret_cast<PlanHeader*>(ws), reinterpret_cast<int32_t*>(ws + ck.w.cu_off),
-                     reinterpret_cast<int2*>(ws + ck.w.items_off), ck.w.max_items);
+                     reinterpret_cast<int4*>(ws + ck.w.items_off), ck.w.max_items);
   ALS_HIP_CHECK(hipGetLastError());
   return AS_OK;
 }
@@ -996,7 +1027,10 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
   if (st != AS_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  if (!(p->flags & AS_ATTN_REUSE_PLAN)) {
+  // When the host lengths show that no request needs more than one chunk,
+  // item i is request i and neither the plan nor the combine kernel runs.
+  const bool direct = ck.exact && !ck.any_split;
+  if (!direct && !(p->flags & AS_ATTN_REUSE_PLAN)) {
     st = run_plan(*p, ck, kv_lens, ws, s);
     if (st != AS_OK) return st;
   }
@@ -1063,7 +1097,7 @@ extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks
   if (st != AS_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  if (!(p->flags & AS_ATTN_REUSE_PLAN)) {
+  if (!(ck.exact && !ck.any_split) && !(p->flags & AS_ATTN_REUSE_PLAN)) {
     st = run_plan(*p, ck, kv_lens, ws, s);
     if (st != AS_OK) return st;
   }
