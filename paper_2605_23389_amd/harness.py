@@ -93,3 +93,15 @@ def fetch_request_kv(pool: DevicePool, request: int):
     k = pool.k.index_select(0, ids).float().cpu().numpy()
     v = pool.v.index_select(0, ids).float().cpu().numpy()
     return k, v, np.arange(nb, dtype=np.int32)
+
+
+def fetch_request_head(pool: DevicePool, request: int, kv_head: int):
+    """One request's logical K and V for one KV head as float32 [L][D] host
+    arrays (sampled oracle checks on full-size pools)."""
+    import torch
+    L = int(pool.kv_lens[request])
+    nb = (L + wl.BLOCK_SIZE - 1) // wl.BLOCK_SIZE
+    ids = torch.from_numpy(pool.block_table[request, :nb].astype(np.int64)).to(pool.k.device)
+    k = pool.k.index_select(0, ids)[:, kv_head].reshape(nb * wl.BLOCK_SIZE, -1)[:L].float().cpu().numpy()
+    v = pool.v.index_select(0, ids)[:, kv_head].reshape(nb * wl.BLOCK_SIZE, -1)[:L].float().cpu().numpy()
+    return k, v

@@ -1,0 +1,84 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+times: the 1024-request, 31.6 GB MHA workload (aligned and random batches)
+and the GQA long-context batch.  The oracle cannot do whole batches at this
+size, so sampled (request, head) outputs are checked one by one, plus
+properties that hold at any size (every output finite; every request
+written)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import attention as oa
+from paper_2605_23389_amd import harness
+from paper_2605_23389_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(lib, pool, batch, ws=None):
+    import torch
+    batch.out.fill_(float("nan"))
+    lib.decode_attention(batch.q, pool.k, pool.v, batch.block_table, batch.kv_lens, batch.out,
+                         kv_lens_host=batch.kv_lens_host, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(batch.out.float()).all()
+
+
+def _check_samples(pool, batch, samples, tol, G):
+    D = pool.head_dim
+    worst = 0.0
+    for (i, kvh) in samples:
+        req = int(batch.members[i])
+        K, V = harness.fetch_request_head(pool, req, kvh)
+        for g in range(G):
+            hq = kvh * G + g
+            q = batch.q[i, hq].float().cpu().numpy()
+            ref = oa.attention_single(q, K, V, 1.0 / math.sqrt(D))
+            got = batch.out[i, hq].double().cpu().numpy()
+            worst = max(worst, float(np.abs(got - ref).max()))
+    assert worst <= tol, f"max-abs err {worst:.3e}"
+    return worst
+
+
+def test_full_size_mha_workload_sampled(lib):
+    """configs[2]: aligned batches 0 (longest, 32768-token requests), 7 and 15
+    (shortest) and random batch 3; bf16 out as in the benchmark; 1.5e-2."""
+    lens = wl.config_lengths(2)
+    pool = harness.make_device_pool(lens, 32, 32, 128, dtype="bf16", seed=0)
+    order, offs = lib.aligned_batch(lens, 64)
+    batches = harness.make_device_batches(pool, order, offs, seed=0)
+    r_order, r_offs = wl.random_grouping(len(lens), 64, seed=0)
+    r_batches = harness.make_device_batches(pool, r_order, r_offs, seed=0)
+    rng = np.random.default_rng(0)
+    for b in (batches[0], batches[7], batches[15], r_batches[3]):
+        _run(lib, pool, b)
+        picks = [(int(i), int(h)) for i, h in zip(rng.integers(0, 64, 5), rng.integers(0, 32, 5))]
+        picks += [(0, 0), (63, 31), (int(np.argmax(b.kv_lens_host)), 7), (int(np.argmin(b.kv_lens_host)), 19)]
+        _check_samples(pool, b, picks, 1.5e-2, G=1)
+
+
+def test_full_size_gqa_long_context_sampled(lib):
+    """configs[3]: batch 128, 64 q / 8 kv heads, D 128, U{4096..32768}: the
+    matrix-core kernel with split-KV at full size; fp32 out; 1.5e-2."""
+    import torch
+    lens = wl.config_lengths(3)
+    pool = harness.make_device_pool(lens, 64, 8, 128, dtype="bf16", seed=3)
+    b = harness.make_device_batches(pool, np.arange(len(lens)), np.array([0, len(lens)]), seed=9,
+                                    out_dtype=torch.float32)[0]
+    _run(lib, pool, b)
+    rng = np.random.default_rng(1)
+    picks = [(int(i), int(h)) for i, h in zip(rng.integers(0, 128, 4), rng.integers(0, 8, 4))]
+    picks += [(int(np.argmax(lens)), 0), (int(np.argmin(lens)), 7)]
+    _check_samples(pool, b, picks, 1.5e-2, G=8)
+
+
+def test_full_size_7b_ragged_batch_whole(lib):
+    """configs[1]: the whole ragged batch of 64 (89 875 tokens) against the
+    oracle for 6 complete requests (all 32 heads)."""
+    lens = wl.config_lengths(1)
+    pool = harness.make_device_pool(lens, 32, 32, 128, dtype="bf16", seed=11)
+    b = harness.make_device_batches(pool, np.arange(64), np.array([0, 64]), seed=7)[0]
+    _run(lib, pool, b)
+    picks = [(i, h) for i in (0, 13, 27, 40, 55, 63) for h in range(32)]
+    _check_samples(pool, b, picks, 1.5e-2, G=1)
