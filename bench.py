@@ -179,6 +179,8 @@ def main():
     ap.add_argument("--skip-extra", action="store_true",
                     help="only the headline pass (used for profiling runs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--only-cfg3", action="store_true",
+                    help="profiling aid: run only the GQA long-context batch (configs[3]) and print its line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 2 GiB device-to-device copies (a kernel of known "
                          "traffic, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -196,6 +198,33 @@ def main():
     als.load()
     torch.cuda.set_device(0)
     dev_name = torch.cuda.get_device_name(0)
+    if args.only_cfg3:
+        if args.copy_calibration:
+            src = torch.empty(1 << 31, dtype=torch.uint8, device="cuda").fill_(1)
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        sh3 = wl.CONFIG_SHAPES[3]
+        lens3 = wl.config_lengths(3, args.seed)
+        pool3 = harness.make_device_pool(lens3, sh3["num_q_heads"], sh3["num_kv_heads"], sh3["head_dim"],
+                                         dtype="bf16", seed=args.seed + 3)
+        b3 = harness.make_device_batches(pool3, np.arange(len(lens3)), np.array([0, len(lens3)]), seed=9)[0]
+        bytes3 = traffic.attention_bytes(lens3, sh3["num_q_heads"], sh3["num_kv_heads"], sh3["head_dim"], 2, 2)
+        p3 = als.attn_params(b3.q, pool3.k, b3.block_table, b3.out, chunk_tokens=args.chunk_tokens)
+        ws3 = torch.empty(als.decode_attention_workspace(p3, b3.tokens), dtype=torch.uint8, device="cuda")
+
+        def attend3():
+            als.decode_attention(b3.q, pool3.k, pool3.v, b3.block_table, b3.kv_lens, b3.out,
+                                 kv_lens_host=b3.kv_lens_host, workspace=ws3, params=p3)
+        for _ in range(args.warmup):
+            attend3()
+        s3 = time_region(attend3, args.steps, torch) / args.steps
+        print(json.dumps({"workload": "configs[3] GQA long context", "us": round(s3 * 1e6, 1),
+                          "alg_bytes": int(bytes3), "GBs": round(bytes3 / s3 / 1e9, 0)}), flush=True)
+        return
+
     shape = wl.CONFIG_SHAPES[2]
     Hq, Hkv, D = shape["num_q_heads"], shape["num_kv_heads"], shape["head_dim"]
     B = 64

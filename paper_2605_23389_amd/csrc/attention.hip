@@ -399,41 +399,44 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a) {
   const size_t block_stride = static_cast<size_t>(Hkv) * kSlabBytes;
 
   u32x4 kA[NLD], vA[NLD], kB[NLD], vB[NLD];
+  auto tile_off = [&](int i) {
+    return static_cast<size_t>(__builtin_amdgcn_readlane(my_id, i)) * block_stride + head_off;
+  };
   if (my_tiles > 0) {
-    const size_t off = static_cast<size_t>(__builtin_amdgcn_readlane(my_id, 0)) * block_stride + head_off;
+    const size_t off = tile_off(0);
     load_tile<T, D>(kA, a.k_blocks + off, lane);
     load_tile<T, D>(vA, a.v_blocks + off, lane);
   }
-  // only the chunk's last tile can be partial
-  const int last_tile = ntiles - 1;
-  const bool last_partial = (ntok % kBlock) != 0;
-
-  for (int i = 0; i < my_tiles; i += 2) {
-    const bool haveB = i + 1 < my_tiles;
-    if (haveB) {
-      const size_t off = static_cast<size_t>(__builtin_amdgcn_readlane(my_id, i + 1)) * block_stride + head_off;
+  // Only the chunk's last tile can be partial.  The hot loop takes pairs of
+  // full tiles with the unmasked code; at most two tiles are left for the
+  // masked code after it.
+  const bool owns_partial = (ntok % kBlock) != 0 && ((ntiles - 1) % kWaves) == wave;
+  const int full_tiles = my_tiles - (owns_partial ? 1 : 0);
+  int i = 0;
+  for (; i + 2 <= full_tiles; i += 2) {
+    {
+      const size_t off = tile_off(i + 1);
       load_tile<T, D>(kB, a.k_blocks + off, lane);
       load_tile<T, D>(vB, a.v_blocks + off, lane);
     }
-    {
-      const int tile = wave + kWaves * i;
-      if (last_partial && tile == last_tile)
-        consume_tile<T, D, G, true>(kA, vA, qr, st, c, t0 + tile * kBlock, kv_len, lane);
-      else
-        consume_tile<T, D, G, false>(kA, vA, qr, st, c, 0, 0, lane);
-    }
+    consume_tile<T, D, G, false>(kA, vA, qr, st, c, 0, 0, lane);
     if (i + 2 < my_tiles) {
-      const size_t off = static_cast<size_t>(__builtin_amdgcn_readlane(my_id, i + 2)) * block_stride + head_off;
+      const size_t off = tile_off(i + 2);
       load_tile<T, D>(kA, a.k_blocks + off, lane);
       load_tile<T, D>(vA, a.v_blocks + off, lane);
     }
+    consume_tile<T, D, G, false>(kB, vB, qr, st, c, 0, 0, lane);
+  }
+  if (i < my_tiles) {
+    const bool haveB = i + 1 < my_tiles;
     if (haveB) {
-      const int tile = wave + kWaves * (i + 1);
-      if (last_partial && tile == last_tile)
-        consume_tile<T, D, G, true>(kB, vB, qr, st, c, t0 + tile * kBlock, kv_len, lane);
-      else
-        consume_tile<T, D, G, false>(kB, vB, qr, st, c, 0, 0, lane);
+      const size_t off = tile_off(i + 1);
+      load_tile<T, D>(kB, a.k_blocks + off, lane);
+      load_tile<T, D>(vB, a.v_blocks + off, lane);
     }
+    consume_tile<T, D, G, true>(kA, vA, qr, st, c, t0 + (wave + kWaves * i) * kBlock, kv_len, lane);
+    if (haveB)
+      consume_tile<T, D, G, true>(kB, vB, qr, st, c, t0 + (wave + kWaves * (i + 1)) * kBlock, kv_len, lane);
   }
 
   // merge the 64/LPT token groups of the wave (lanes that hold the same dims)
@@ -865,9 +868,9 @@ int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
   // Long chunks amortise a workgroup's start-up (dependent loads of the item,
   // the block ids and the first tile) and its merge; short chunks balance the
   // tail of the launch.  Measured on MI355X the longest chunk wins as long as
-  // the launch keeps a few thousand workgroups, so: the largest power of two
-  // in [256, 4096] that still leaves about 16 workgroups per compute unit.
-  const int64_t want_items = 256 * 16;
+  // the launch keeps a thousand or more workgroups, so: the largest power of
+  // two in [256, 4096] that still leaves about 4 workgroups per compute unit.
+  const int64_t want_items = 256 * 4;
   const int64_t c = total_tokens * p.num_kv_heads / want_items;
   int chunk = 256;
   while (chunk < kMaxChunk && chunk * 2 <= c) chunk *= 2;
