@@ -77,6 +77,55 @@ as_status as_aligned_batch(const int32_t* kv_lens, int32_t n, int32_t batch_size
                            int32_t* order, int32_t* batch_offsets, int32_t* num_batches);
 
 /* --------------------------------------------------------------------------
+ * The paper's own batch generator (Section 3.3, Algorithm 1): a quad-tree over
+ * prefix lengths [1, max_len] (longer prefixes are clamped, Section 4.1) whose
+ * internal nodes carry (request counter, block counter), and Density First
+ * Search over it.  Host only.
+ *   as_qtree_create      max_len / leaf_width must be a power of four (the
+ *                        paper's range is 65536; leaf_width is this library's
+ *                        parameter, e.g. 16 tokens = one KV block)
+ *   as_qtree_insert      adds request (id, prefix_len >= 1, blocks >= 1);
+ *                        `now` stamps sub-trees that were empty (Section 3.5)
+ *   as_qtree_remove      removes a request by id
+ *   as_qtree_size        request / block counters of the root
+ *   as_qtree_next_batch  one search: case 1 (sub-tree fits b_max and holds
+ *                        >= k_min requests: taken whole), case 2 (exceeds
+ *                        b_max: descend into the child with the most requests,
+ *                        leftmost on ties; at a leaf, requests are taken in
+ *                        (length, id) order while they fit, at least one),
+ *                        case 3 (fits but < k_min: widened with at most
+ *                        k_min - |batch| requests of the nearest siblings --
+ *                        left siblings if any, else right -- stopping at the
+ *                        first that exceeds the remaining budget).  With
+ *                        starve_after >= 0 the search starts at the non-empty
+ *                        internal node whose age now - stamp is largest and
+ *                        above starve_after (pass a negative value to switch
+ *                        this off).  The batch's requests are removed from
+ *                        the tree; their ids are written to out_ids[0..*out_n)
+ *                        (node's own requests by (length, id), then the
+ *                        additions); *out_case (optional) is 1, 2 or 3.
+ *                        *out_n = 0 when the tree is empty.
+ *   as_dfs_batches       convenience: insert n requests (id = index), generate
+ *                        batches until the tree is empty; order[n],
+ *                        batch_offsets[n + 1] caller-allocated.
+ * Errors: AS_EINVAL (null, bad geometry, duplicate / unknown id, non-positive
+ * values), AS_ERANGE (capacity too small; nothing is removed then).
+ * -------------------------------------------------------------------------- */
+typedef struct as_qtree as_qtree;
+as_status as_qtree_create(as_qtree** out, int32_t max_len, int32_t leaf_width);
+as_status as_qtree_destroy(as_qtree* t);
+as_status as_qtree_insert(as_qtree* t, int32_t request_id, int32_t prefix_len, int32_t blocks,
+                          double now);
+as_status as_qtree_remove(as_qtree* t, int32_t request_id);
+as_status as_qtree_size(const as_qtree* t, int64_t* requests, int64_t* blocks);
+as_status as_qtree_next_batch(as_qtree* t, int64_t b_max, int32_t k_min, double now,
+                              double starve_after, int32_t* out_ids, int32_t capacity,
+                              int32_t* out_n, int32_t* out_case);
+as_status as_dfs_batches(const int32_t* kv_lens, const int32_t* blocks, int32_t n, int64_t b_max,
+                         int32_t k_min, int32_t max_len, int32_t leaf_width, int32_t* order,
+                         int32_t* batch_offsets, int32_t* num_batches);
+
+/* --------------------------------------------------------------------------
  * Decode-iteration attention (paper Section 2.2, Eq. 2):
  *   out[b][h] = softmax(q[b][h] . K_b^T / sqrt(d_k)) V_b
  * for the newest token's query of every request b against all kv_lens[b]

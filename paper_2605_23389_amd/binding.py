@@ -27,6 +27,8 @@ EXPORTS = [
     "as_decode_attention", "as_stage_kv", "as_unstage_kv", "as_pipeline_create",
     "as_pipeline_stream", "as_pipeline_begin_stage", "as_pipeline_end_stage",
     "as_pipeline_acquire", "as_pipeline_release", "as_pipeline_destroy", "as_kv_read_sweep",
+    "as_qtree_create", "as_qtree_destroy", "as_qtree_insert", "as_qtree_remove", "as_qtree_size",
+    "as_qtree_next_batch", "as_dfs_batches",
 ]
 
 
@@ -93,6 +95,22 @@ def load() -> C.CDLL:
         getattr(lib, name).argtypes = [vp, C.c_int32, vp]
     lib.as_pipeline_destroy.restype = C.c_int
     lib.as_pipeline_destroy.argtypes = [vp]
+    lib.as_qtree_create.restype = C.c_int
+    lib.as_qtree_create.argtypes = [C.POINTER(vp), C.c_int32, C.c_int32]
+    lib.as_qtree_destroy.restype = C.c_int
+    lib.as_qtree_destroy.argtypes = [vp]
+    lib.as_qtree_insert.restype = C.c_int
+    lib.as_qtree_insert.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_double]
+    lib.as_qtree_remove.restype = C.c_int
+    lib.as_qtree_remove.argtypes = [vp, C.c_int32]
+    lib.as_qtree_size.restype = C.c_int
+    lib.as_qtree_size.argtypes = [vp, i64p, i64p]
+    lib.as_qtree_next_batch.restype = C.c_int
+    lib.as_qtree_next_batch.argtypes = [vp, C.c_int64, C.c_int32, C.c_double, C.c_double, i32p,
+                                        C.c_int32, i32p, i32p]
+    lib.as_dfs_batches.restype = C.c_int
+    lib.as_dfs_batches.argtypes = [i32p, i32p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                   i32p, i32p, i32p]
     _lib = lib
     return lib
 
@@ -275,3 +293,63 @@ class Pipeline:
             self.destroy()
         except Exception:
             pass
+
+
+# ---------------------------------------------------------------------------
+# quad-tree + Density First Search batch generator
+# ---------------------------------------------------------------------------
+class QuadTree:
+    """The paper's batch generator: quad-tree over prefix lengths + Density
+    First Search (argument marshalling over as_qtree_*)."""
+
+    def __init__(self, max_len: int = 65536, leaf_width: int = 16):
+        self._h = C.c_void_p()
+        _check(load().as_qtree_create(C.byref(self._h), int(max_len), int(leaf_width)))
+
+    def insert(self, request_id: int, prefix_len: int, blocks: int, now: float = 0.0):
+        _check(load().as_qtree_insert(self._h, int(request_id), int(prefix_len), int(blocks), float(now)))
+
+    def remove(self, request_id: int):
+        _check(load().as_qtree_remove(self._h, int(request_id)))
+
+    def size(self):
+        r, b = C.c_int64(), C.c_int64()
+        _check(load().as_qtree_size(self._h, C.byref(r), C.byref(b)))
+        return r.value, b.value
+
+    def __len__(self):
+        return self.size()[0]
+
+    def next_batch(self, b_max: int, k_min: int, now: float = 0.0, starve_after=None):
+        """Returns (ids, case) of one generated batch; ([], 0) when empty."""
+        cap = max(len(self), 1)
+        ids = np.empty(cap, dtype=np.int32)
+        n, case = C.c_int32(0), C.c_int32(0)
+        _check(load().as_qtree_next_batch(self._h, int(b_max), int(k_min), float(now),
+                                          -1.0 if starve_after is None else float(starve_after),
+                                          _ptr(ids, C.c_int32), cap, C.byref(n), C.byref(case)))
+        return ids[: n.value].tolist(), case.value
+
+    def destroy(self):
+        if self._h:
+            h, self._h = self._h, C.c_void_p()
+            _check(load().as_qtree_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def dfs_batches(kv_lens, blocks, b_max: int, k_min: int, max_len: int = 65536, leaf_width: int = 16):
+    """All requests through the quad-tree generator; returns (order, batch_offsets)."""
+    lens, blk = _i32(kv_lens), _i32(blocks)
+    n = int(lens.shape[0])
+    order = np.empty(max(n, 1), dtype=np.int32)
+    offsets = np.empty(n + 1, dtype=np.int32)
+    nb = C.c_int32(0)
+    _check(load().as_dfs_batches(_ptr(lens, C.c_int32), _ptr(blk, C.c_int32), n, int(b_max), int(k_min),
+                                 int(max_len), int(leaf_width), _ptr(order, C.c_int32),
+                                 _ptr(offsets, C.c_int32), C.byref(nb)))
+    return order[:n], offsets[: nb.value + 1]
