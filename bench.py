@@ -355,6 +355,46 @@ def main():
         }
         log(f"random: {gpu_r * 1e3:.3f} ms/pass vs aligned {gpu_s / args.steps * 1e3:.3f}")
 
+        # ---------------- batch generators: sort-and-chunk vs the paper's quad-tree DFS
+        blocks_all = ((lens.astype(np.int64) + 15) // 16).astype(np.int32)
+        b_max = int(0.4 * blocks_all.sum())          # 40 % of the pool's blocks (paper Section 4.1)
+
+        def host_us(fn, reps=20):
+            fn()
+            t = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            return (time.perf_counter() - t) / reps * 1e6
+        us_sort = host_us(lambda: als.aligned_batch(lens, B))
+        us_dfs = host_us(lambda: als.dfs_batches(lens, blocks_all, b_max, 36))
+        order_d, offs_d = als.dfs_batches(lens, blocks_all, b_max, 36)
+        batches_d = harness.make_device_batches(pool, order_d, offs_d, seed=args.seed)
+        ws_d = torch.empty(max(als.decode_attention_workspace(params_for(b), b.tokens) for b in batches_d),
+                           dtype=torch.uint8, device="cuda")
+        for b in batches_d:
+            b.params = params_for(b)
+            b.bytes = traffic.attention_bytes(b.kv_lens_host, Hq, Hkv, D, 2, 2)
+
+        def step_dfs():
+            for b in batches_d:
+                als.decode_attention(b.q, pool.k, pool.v, b.block_table, b.kv_lens, b.out,
+                                     kv_lens_host=b.kv_lens_host, workspace=ws_d, params=b.params)
+        step_dfs()
+        gpu_d = time_region(step_dfs, 5, torch) / 5
+        sizes = [int(b.kv_lens_host.shape[0]) for b in batches_d]
+        result["batch_generators"] = {
+            "sort_and_chunk_us": round(us_sort, 1), "quadtree_dfs_us": round(us_dfs, 1),
+            "quadtree_dfs": {"b_max_blocks": b_max, "k_min": 36, "num_batches": len(batches_d),
+                             "batch_size_min": min(sizes), "batch_size_max": max(sizes),
+                             "sum_batch_max": int(sum(int(b.kv_lens_host.max()) for b in batches_d)),
+                             "ms_per_pass": round(gpu_d * 1e3, 3),
+                             "GBs": round(sum(b.bytes for b in batches_d) / gpu_d / 1e9, 0)},
+            "note": "host time to batch the 1024 requests; the quad-tree generator (Alg. 1) forms "
+                    "variable-size batches under a block budget, sort-and-chunk fixed-size ones",
+        }
+        log(f"batchers: sort {us_sort:.1f} us, dfs {us_dfs:.1f} us; dfs pass {gpu_d * 1e3:.3f} ms in {len(batches_d)} batches")
+        del batches_d, ws_d
+
         # ---------------- streaming-read ceiling on the largest aligned batches
         cks = torch.zeros(256, dtype=torch.int32, device="cuda")
 

@@ -866,14 +866,23 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab
 int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
   if (p.chunk_tokens > 0) return p.chunk_tokens;
   // Long chunks amortise a workgroup's start-up (dependent loads of the item,
-  // the block ids and the first tile) and its merge; short chunks balance the
-  // tail of the launch.  Measured on MI355X the longest chunk wins as long as
-  // the launch keeps a thousand or more workgroups, so: the largest power of
-  // two in [256, 4096] that still leaves about 4 workgroups per compute unit.
-  const int64_t want_items = 256 * 4;
-  const int64_t c = total_tokens * p.num_kv_heads / want_items;
-  int chunk = 256;
-  while (chunk < kMaxChunk && chunk * 2 <= c) chunk *= 2;
+  // the block ids and the first tile) and its merge; short chunks shorten the
+  // tail of the launch, where the last workgroups run next to idle compute
+  // units.  With a per-item overhead worth o tokens, S concurrently resident
+  // workgroups and a tail of about half a chunk, the cost
+  //   o * (T / chunk) / S + chunk / 2          (T = tokens * KV heads)
+  // is smallest at chunk = sqrt(2 o T / S); o ~ 128 tokens and S ~ 1024 were
+  // fitted to sweeps on MI355X (optimum ~900 tokens for a 90 k-token ragged MHA
+  // batch, ~2-4 k tokens for 0.6-2.4 M-token batches).
+  const double t = static_cast<double>(total_tokens) * p.num_kv_heads;
+  // the grouped-query (matrix-core) kernel merges and writes up to 16 heads
+  // per item: its per-item overhead is about 4x, so its best chunk about 2x
+  const int group = p.num_q_heads / p.num_kv_heads;
+  const bool wide = p.dtype == AS_DTYPE_BF16 && p.head_dim == 128 && group >= 4;
+  int chunk = static_cast<int>(std::sqrt(wide ? t : t / 4.0));
+  chunk = (chunk + 63) / 64 * 64;
+  if (chunk < 256) chunk = 256;
+  if (chunk > kMaxChunk) chunk = kMaxChunk;
   return chunk;
 }
 
@@ -923,11 +932,16 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
   out->total_tokens = total;
   out->chunk = pick_chunk(*p, total);
   if (kv_lens_host && p->chunk_tokens == 0) {
-    // a batch of short requests: one chunk per request, so that neither the
-    // plan nor the combine kernel is needed
+    // One chunk per request needs neither the plan nor the combine kernel.
+    // Taken when requests are short, or not much longer than the chunk the
+    // cost model picked, or when the batch is length-aligned (longest request
+    // within 1.5x of the mean: workgroups then finish together anyway).
     int max_len = 0;
     for (int b = 0; b < p->batch; ++b) max_len = kv_lens_host[b] > max_len ? kv_lens_host[b] : max_len;
-    if (max_len <= 1024 && out->chunk < max_len) out->chunk = (max_len + kBlock - 1) / kBlock * kBlock;
+    const bool aligned = static_cast<double>(max_len) * p->batch <= 1.5 * static_cast<double>(total);
+    if (out->chunk < max_len &&
+        (max_len <= 1024 || (max_len <= kMaxChunk && (max_len <= 2 * out->chunk || aligned))))
+      out->chunk = (max_len + kBlock - 1) / kBlock * kBlock;
   }
   out->exact = kv_lens_host != nullptr;
   out->any_split = true;
