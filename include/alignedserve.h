@@ -195,6 +195,70 @@ as_status as_decode_attention(const void* q, const void* k_blocks, const void* v
                               size_t workspace_bytes, void* hip_stream);
 
 /* --------------------------------------------------------------------------
+ * KV append (paper Section 2.1: a generated token's key and value join the
+ * request's KVCache and take part in every later iteration).
+ * For every request b of the batch, writes k_new[b] and v_new[b]
+ * (device, [batch][num_kv_heads][head_dim], dtype) to position kv_lens[b] of
+ * its paged cache -- row kv_lens[b] % 16 of block
+ * block_table[b][kv_lens[b] / 16] -- and increments kv_lens[b] (device,
+ * in place).  The block-table entry must already be allocated by the caller.
+ * A request whose table row is full is left untouched.  Uses dtype, batch,
+ * num_kv_heads, head_dim, block_size, num_blocks and max_blocks_per_seq of
+ * the params.  Asynchronous on the stream.
+ * Errors: AS_EINVAL, AS_EUNSUPPORTED, AS_EHIP.
+ * -------------------------------------------------------------------------- */
+as_status as_kv_append(const void* k_new, const void* v_new, void* k_blocks, void* v_blocks,
+                       const int32_t* block_table, int32_t* kv_lens, const as_attn_params* p,
+                       void* hip_stream);
+
+/* --------------------------------------------------------------------------
+ * Batch-level scheduling policy (paper Section 3.4, Algorithm 2).  Host only;
+ * purely logical (ids, lengths, block counts): the caller moves the KV data
+ * the returned events imply (as_stage_kv for admissions, as_unstage_kv for
+ * evictions).
+ *   as_sched_create   total_blocks of HBM, block_size tokens per block,
+ *                     max_batch = cap on the running batch
+ *   as_sched_push_candidate_batch    fill the candidate-batch buffer with a
+ *                     generated batch (origin = its batch number)
+ *   as_sched_push_candidate_request  add one request to the candidate-requests
+ *                     buffer (late arrivals of the running batch's length)
+ *   as_sched_step     one pass after a decode iteration.  advance != 0: every
+ *                     running request has produced a token (kv_len + 1,
+ *                     remaining - 1).  Then: completed requests are released;
+ *                     if the next iteration (one fresh block per running
+ *                     request whose kv_len is a multiple of block_size) does
+ *                     not fit -> case 3: evict the longest request (while two
+ *                     original batches coexist: the longest of the one with
+ *                     the smaller batch number) to the tail of the
+ *                     candidate-requests buffer, repeatedly until it fits;
+ *                     else admit, in buffer order, from the candidate-requests
+ *                     buffer (case 1) or, if that is empty, from the
+ *                     candidate-batch buffer (case 2), while the batch is
+ *                     below max_batch and the request's blocks plus the next
+ *                     iteration's growth fit; stops at the first that does
+ *                     not.  Outputs: ids of completed / evicted / admitted
+ *                     requests (arrays of `capacity` >= max(max_batch, running
+ *                     size) entries each) and the case (0 = nothing admitted
+ *                     or evicted).
+ *   as_sched_state / as_sched_running   inspection.
+ * Errors: AS_EINVAL, AS_ERANGE (capacity).
+ * -------------------------------------------------------------------------- */
+typedef struct as_sched as_sched;
+as_status as_sched_create(as_sched** out, int64_t total_blocks, int32_t block_size, int32_t max_batch);
+as_status as_sched_destroy(as_sched* s);
+as_status as_sched_push_candidate_batch(as_sched* s, int32_t origin, const int32_t* ids,
+                                        const int32_t* kv_lens, const int32_t* remaining, int32_t n);
+as_status as_sched_push_candidate_request(as_sched* s, int32_t origin, int32_t id, int32_t kv_len,
+                                          int32_t remaining);
+as_status as_sched_step(as_sched* s, int32_t advance, int32_t* completed, int32_t* n_completed,
+                        int32_t* evicted, int32_t* n_evicted, int32_t* admitted, int32_t* n_admitted,
+                        int32_t capacity, int32_t* which_case);
+as_status as_sched_state(const as_sched* s, int64_t* free_blocks, int32_t* n_running,
+                         int32_t* n_candidate_requests, int32_t* n_candidate_batch);
+as_status as_sched_running(const as_sched* s, int32_t* ids, int32_t* kv_lens, int32_t* origins,
+                           int32_t capacity, int32_t* n);
+
+/* --------------------------------------------------------------------------
  * KV staging: host KV pool -> HBM block pool (paper Section 3.2: the KV pool
  * lives in host memory and a scheduled batch's KVCache is migrated to the
  * decoding GPU, directly over PCIe when no peer GPU serves as a buffer; the

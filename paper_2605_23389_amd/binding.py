@@ -28,7 +28,9 @@ EXPORTS = [
     "as_pipeline_stream", "as_pipeline_begin_stage", "as_pipeline_end_stage",
     "as_pipeline_acquire", "as_pipeline_release", "as_pipeline_destroy", "as_kv_read_sweep",
     "as_qtree_create", "as_qtree_destroy", "as_qtree_insert", "as_qtree_remove", "as_qtree_size",
-    "as_qtree_next_batch", "as_dfs_batches",
+    "as_qtree_next_batch", "as_dfs_batches", "as_kv_append", "as_sched_create", "as_sched_destroy",
+    "as_sched_push_candidate_batch", "as_sched_push_candidate_request", "as_sched_step",
+    "as_sched_state", "as_sched_running",
 ]
 
 
@@ -95,6 +97,22 @@ def load() -> C.CDLL:
         getattr(lib, name).argtypes = [vp, C.c_int32, vp]
     lib.as_pipeline_destroy.restype = C.c_int
     lib.as_pipeline_destroy.argtypes = [vp]
+    lib.as_kv_append.restype = C.c_int
+    lib.as_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, C.POINTER(AttnParams), vp]
+    lib.as_sched_create.restype = C.c_int
+    lib.as_sched_create.argtypes = [C.POINTER(vp), C.c_int64, C.c_int32, C.c_int32]
+    lib.as_sched_destroy.restype = C.c_int
+    lib.as_sched_destroy.argtypes = [vp]
+    lib.as_sched_push_candidate_batch.restype = C.c_int
+    lib.as_sched_push_candidate_batch.argtypes = [vp, C.c_int32, i32p, i32p, i32p, C.c_int32]
+    lib.as_sched_push_candidate_request.restype = C.c_int
+    lib.as_sched_push_candidate_request.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.as_sched_step.restype = C.c_int
+    lib.as_sched_step.argtypes = [vp, C.c_int32, i32p, i32p, i32p, i32p, i32p, i32p, C.c_int32, i32p]
+    lib.as_sched_state.restype = C.c_int
+    lib.as_sched_state.argtypes = [vp, i64p, i32p, i32p, i32p]
+    lib.as_sched_running.restype = C.c_int
+    lib.as_sched_running.argtypes = [vp, i32p, i32p, i32p, C.c_int32, i32p]
     lib.as_qtree_create.restype = C.c_int
     lib.as_qtree_create.argtypes = [C.POINTER(vp), C.c_int32, C.c_int32]
     lib.as_qtree_destroy.restype = C.c_int
@@ -353,3 +371,69 @@ def dfs_batches(kv_lens, blocks, b_max: int, k_min: int, max_len: int = 65536, l
                                  int(max_len), int(leaf_width), _ptr(order, C.c_int32),
                                  _ptr(offsets, C.c_int32), C.byref(nb)))
     return order[:n], offsets[: nb.value + 1]
+
+
+# ---------------------------------------------------------------------------
+# decode loop: KV append and the batch-level scheduler
+# ---------------------------------------------------------------------------
+def kv_append(k_new, v_new, k_blocks, v_blocks, block_table, kv_lens, stream=None):
+    """Append one token's K/V per request to the paged cache; kv_lens (device
+    int32) is incremented in place."""
+    NB, Hkv, bs, D = k_blocks.shape
+    params = AttnParams(dtype=_torch_dtype_code(k_blocks), out_dtype=_torch_dtype_code(k_blocks),
+                        batch=kv_lens.shape[0], num_q_heads=Hkv, num_kv_heads=Hkv, head_dim=D,
+                        block_size=bs, num_blocks=NB, max_blocks_per_seq=block_table.shape[1],
+                        scale=0.0, chunk_tokens=0, flags=0)
+    _check(load().as_kv_append(k_new.data_ptr(), v_new.data_ptr(), k_blocks.data_ptr(), v_blocks.data_ptr(),
+                               block_table.data_ptr(), kv_lens.data_ptr(), C.byref(params),
+                               _stream_ptr(stream)))
+
+
+class Scheduler:
+    """Batch-level scheduling policy (marshalling over as_sched_*)."""
+
+    def __init__(self, total_blocks: int, block_size: int = 16, max_batch: int = 64):
+        self._h = C.c_void_p()
+        self.max_batch = int(max_batch)
+        _check(load().as_sched_create(C.byref(self._h), int(total_blocks), int(block_size), int(max_batch)))
+
+    def push_candidate_batch(self, origin, ids, kv_lens, remaining):
+        i, l, r = _i32(ids), _i32(kv_lens), _i32(remaining)
+        _check(load().as_sched_push_candidate_batch(self._h, int(origin), _ptr(i, C.c_int32),
+                                                    _ptr(l, C.c_int32), _ptr(r, C.c_int32), int(i.shape[0])))
+
+    def push_candidate_request(self, origin, rid, kv_len, remaining):
+        _check(load().as_sched_push_candidate_request(self._h, int(origin), int(rid), int(kv_len), int(remaining)))
+
+    def state(self):
+        f, a, b, c = C.c_int64(), C.c_int32(), C.c_int32(), C.c_int32()
+        _check(load().as_sched_state(self._h, C.byref(f), C.byref(a), C.byref(b), C.byref(c)))
+        return dict(free_blocks=f.value, running=a.value, candidate_requests=b.value, candidate_batch=c.value)
+
+    def running(self):
+        cap = max(self.state()["running"], 1)
+        ids, lens, org = (np.empty(cap, dtype=np.int32) for _ in range(3))
+        n = C.c_int32()
+        _check(load().as_sched_running(self._h, _ptr(ids, C.c_int32), _ptr(lens, C.c_int32),
+                                       _ptr(org, C.c_int32), cap, C.byref(n)))
+        return ids[: n.value].copy(), lens[: n.value].copy(), org[: n.value].copy()
+
+    def step(self, advance: bool = True):
+        cap = max(self.state()["running"], self.max_batch)
+        done, ev, ad = (np.empty(cap, dtype=np.int32) for _ in range(3))
+        nd, ne, na, case = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+        _check(load().as_sched_step(self._h, 1 if advance else 0, _ptr(done, C.c_int32), C.byref(nd),
+                                    _ptr(ev, C.c_int32), C.byref(ne), _ptr(ad, C.c_int32), C.byref(na),
+                                    cap, C.byref(case)))
+        return done[: nd.value].tolist(), ev[: ne.value].tolist(), ad[: na.value].tolist(), case.value
+
+    def destroy(self):
+        if self._h:
+            h, self._h = self._h, C.c_void_p()
+            _check(load().as_sched_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(HERE, "libalignedserve.so")
 
-SOURCES = ["batcher.cpp", "quadtree.cpp", "stage.hip", "attention.hip"]
+SOURCES = ["batcher.cpp", "quadtree.cpp", "scheduler.cpp", "stage.hip", "append.hip", "attention.hip"]
 
 # packed-fp32 VALU forms are switched off for all device code (they have
 # produced silently wrong results on the test machines)
