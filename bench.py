@@ -340,11 +340,14 @@ def main():
         rows_a = per_batch(batches_a)
         for _ in range(2):
             step_random()
-        gpu_r = time_region(step_random, max(args.steps // 2, 3), torch) / max(args.steps // 2, 3)
+        # per-pass times, median: a single disturbed pass must not decide the comparison
+        gpu_r = float(np.median([time_region(step_random, 1, torch) for _ in range(max(args.steps // 2, 5))]))
+        gpu_a_med = float(np.median([time_region(step_aligned, 1, torch) for _ in range(max(args.steps // 2, 5))]))
         rows_r = per_batch(batches_r)
         bytes_r = sum(b.bytes for b in batches_r)
         result["aligned_vs_random"] = {
             "aligned": {"ms_per_pass": round(gpu_s / args.steps * 1e3, 3),
+                        "ms_per_pass_median": round(gpu_a_med * 1e3, 3),
                         "GBs": round(bytes_a / (gpu_s / args.steps) / 1e9, 0),
                         "tokens_per_s": round(n / (gpu_s / args.steps), 0),
                         "sum_batch_max": int(sum(r["max_len"] for r in rows_a)), "batches": rows_a},
@@ -527,6 +530,12 @@ def main():
         }
         log(f"cpu oracle: {done_bytes / cpu_s / 1e9:.3f} GB/s on {cores} threads")
 
+    result["paper_context"] = {
+        "note": "whole-system numbers the paper reports on other hardware (context, not a target)",
+        "max_decode_throughput_gain": "1.98x over vLLM / DistServe / FastGen (LongBench, AzurePublicDataset)",
+        "max_p99_tpot_reduction": "7.4x (AzurePublicDataset)",
+        "hardware": "2x Xeon Platinum 8462Y+, 8x NVIDIA H100 with NVLink, 800 GB DRAM, PCIe 5.0, FP16, OPT models",
+    }
     print(json.dumps(result), flush=True)
 
 
