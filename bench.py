@@ -168,6 +168,78 @@ def pipeline_leg(args, torch, als, harness, traffic, wl, log):
     }
 
 
+def paper_shaped_leg(args, torch, als, harness, traffic, wl, log):
+    """Attention-only analogues of the paper's two motivating experiments on
+    the 7B-shaped layer (32 MHA heads x 128, bf16).
+    (a) Section 2.3 / Figure 1: a batch of short requests (32-token prompts
+        after 600 generated tokens) with 0, 1, 2 or 4 long ones (4096-token
+        prompts), batch sizes 32..256: how much a few stragglers stretch the
+        iteration.
+    (b) Section 2.4 / Figure 3: 64 groups x 64 requests with lengths
+        10, 70, ..., 3790; 64 same-length batches vs 64 one-of-each batches."""
+    Hq = Hkv = 32
+    D = 128
+    out = {}
+    # (a)
+    rows = []
+    for B in (32, 64, 128, 256):
+        for n_long in (0, 1, 2, 4):
+            lens = np.full(B, 32 + 600, dtype=np.int32)
+            lens[:n_long] = 4096 + 600
+            pool = harness.make_device_pool(lens, Hq, Hkv, D, dtype="bf16", seed=args.seed + B + n_long)
+            b = harness.make_device_batches(pool, np.arange(B), np.array([0, B]), seed=1)[0]
+            prm = als.attn_params(b.q, pool.k, b.block_table, b.out, chunk_tokens=args.chunk_tokens)
+            ws = torch.empty(als.decode_attention_workspace(prm, b.tokens), dtype=torch.uint8, device="cuda")
+
+            def f():
+                als.decode_attention(b.q, pool.k, pool.v, b.block_table, b.kv_lens, b.out,
+                                     kv_lens_host=b.kv_lens_host, workspace=ws, params=prm)
+            f()
+            t = time_region(f, 30, torch) / 30
+            rows.append({"batch": B, "long": n_long, "us": round(t * 1e6, 1), "tokens": b.tokens})
+            del pool, b, ws
+    out["straggler_mix"] = {"rows": rows,
+                            "note": "paper (whole model, vLLM, H100, batch 64): 13.49 / 18.29 / 19.27 / 21.73 ms "
+                                    "for 0 / 1 / 2 / 4 long requests (+61 %)"}
+    # (b) one pool of 64 slots x 3790 tokens; a same-length batch reads a prefix of every slot
+    group_lens = np.arange(64, dtype=np.int32) * 60 + 10
+    slots = np.full(64, int(group_lens.max()), dtype=np.int32)
+    pool = harness.make_device_pool(slots, Hq, Hkv, D, dtype="bf16", seed=args.seed + 77)
+    ws = None
+    batches = []
+    for g in range(65):
+        lens = np.full(64, group_lens[g], dtype=np.int32) if g < 64 else group_lens.copy()
+        mb = int((int(lens.max()) + 15) // 16)
+        bt = torch.from_numpy(np.ascontiguousarray(pool.block_table[:, :mb])).cuda()
+        q = torch.empty((64, Hq, D), dtype=torch.bfloat16, device="cuda").normal_()
+        o = torch.empty_like(q)
+        prm = als.attn_params(q, pool.k, bt, o, chunk_tokens=args.chunk_tokens)
+        batches.append((lens, torch.from_numpy(lens).cuda(), bt, q, o, prm))
+    need = max(als.decode_attention_workspace(x[5], int(x[0].sum())) for x in batches)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+
+    def run(x):
+        als.decode_attention(x[3], pool.k, pool.v, x[2], x[1], x[4], kv_lens_host=x[0], workspace=ws, params=x[5])
+
+    def same_length_pass():
+        for x in batches[:64]:
+            run(x)
+
+    def mixed_pass():
+        for _ in range(64):
+            run(batches[64])
+    same_length_pass(); mixed_pass()
+    t_same = time_region(same_length_pass, 3, torch) / 3
+    t_mixed = time_region(mixed_pass, 3, torch) / 3
+    out["same_length_vs_mixed"] = {
+        "same_length_ms": round(t_same * 1e3, 3), "mixed_ms": round(t_mixed * 1e3, 3),
+        "ratio_mixed_over_same": round(t_mixed / t_same, 3),
+        "note": "4096 requests, 64 batches of 64; paper (whole model, vLLM): average TPOT about 200 ms for "
+                "same-length batches vs 233.43 ms for one-of-each batches (1.17x)"}
+    log(f"paper-shaped: same-length {t_same * 1e3:.2f} ms vs mixed {t_mixed * 1e3:.2f} ms")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -484,6 +556,13 @@ def main():
         except Exception as e:
             result["decode_loop"] = {"error": repr(e)}
             log(f"decode loop leg failed: {e!r}")
+
+        # ---------------- the paper's two motivating experiments, attention only
+        try:
+            result["paper_shaped"] = paper_shaped_leg(args, torch, als, harness, traffic, wl, log)
+        except Exception as e:
+            result["paper_shaped"] = {"error": repr(e)}
+            log(f"paper-shaped leg failed: {e!r}")
 
         # ---------------- configs[4] (scaled): host-resident KV pipeline
         try:
