@@ -859,7 +859,16 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab
   }
   uint32_t r = x.x ^ x.y ^ x.z ^ x.w;
   for (int off = 32; off > 0; off >>= 1) r ^= __shfl_xor(r, off);
-  if (lane == 0) atomicXor(checksum + (blockIdx.x & 255), r);
+  // one atomic per workgroup
+  __shared__ uint32_t wave_sum[kWaves];
+  if (lane == 0) wave_sum[wave] = r;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t t = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) t ^= wave_sum[w];
+    atomicXor(checksum + (blockIdx.x & 255), t);
+  }
 }
 
 // ------------------------------------------------------------------ host side
