@@ -485,7 +485,8 @@ def main():
 
         # ---------------- configs[1]: one ragged 7B-shaped batch of 64
         lens1 = wl.config_lengths(1, args.seed)
-        pool1 = harness.make_device_pool(lens1, Hq, Hkv, D, dtype="bf16", seed=args.seed + 11)
+        pool1 = harness.make_device_pool(lens1, Hq, Hkv, D, dtype="bf16", seed=args.seed + 11,
+                                         table_seed=args.seed + 11)
         b1 = harness.make_device_batches(pool1, np.arange(64), np.array([0, 64]), seed=7)[0]
         b1.params = als.attn_params(b1.q, pool1.k, b1.block_table, b1.out, chunk_tokens=args.chunk_tokens)
         b1.bytes = traffic.attention_bytes(b1.kv_lens_host, Hq, Hkv, D, 2, 2)
@@ -500,6 +501,41 @@ def main():
                                        "note": "configs[1]: 64 requests, lognormal(1024, s0.8) clip [128,8192]; "
                                                "its 1.5 GB working set is re-read back to back"}
         log(f"cfg1: {s1 * 1e6:.1f} us, {b1.bytes / s1 / 1e9:.0f} GB/s")
+
+        # ---------------- one whole decode iteration of the 7B-shaped model's attention: 32 layers,
+        # each with its own KV pool, the work plan built once and reused, eager and as one HIP graph
+        layers = 32
+        pools = [pool1] + [harness.make_device_pool(lens1, Hq, Hkv, D, dtype="bf16", seed=args.seed + 100 + l,
+                                                    table_seed=args.seed + 11) for l in range(1, layers)]
+        for pl in pools[1:]:
+            assert np.array_equal(pl.block_table, pool1.block_table)
+        p_first = als.attn_params(b1.q, pool1.k, b1.block_table, b1.out, chunk_tokens=args.chunk_tokens)
+        p_reuse = als.attn_params(b1.q, pool1.k, b1.block_table, b1.out, chunk_tokens=args.chunk_tokens,
+                                  flags=als.ATTN_REUSE_PLAN)
+
+        def iteration():
+            for l, pl in enumerate(pools):
+                als.decode_attention(b1.q, pl.k, pl.v, b1.block_table, b1.kv_lens, b1.out,
+                                     kv_lens_host=b1.kv_lens_host, workspace=ws,
+                                     params=p_first if l == 0 else p_reuse)
+        iteration()
+        t_eager = time_region(iteration, 5, torch) / 5
+        cap_stream = torch.cuda.Stream()
+        cap_stream.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(cap_stream):
+            with torch.cuda.graph(graph, stream=cap_stream):
+                iteration()
+        torch.cuda.current_stream().wait_stream(cap_stream)
+        graph.replay()
+        t_graph = time_region(graph.replay, 5, torch) / 5
+        result["cfg1_32_layer_iteration"] = {
+            "layers": layers, "eager_us": round(t_eager * 1e6, 1), "graph_us": round(t_graph * 1e6, 1),
+            "GBs_graph": round(layers * b1.bytes / t_graph / 1e9, 0),
+            "note": "attention of all 32 layers of one decode iteration for the configs[1] batch (47 GB of KV); "
+                    "plan built by layer 0 and reused; 'graph' replays the 32 calls as one captured HIP graph"}
+        log(f"cfg1 x32 layers: eager {t_eager * 1e6:.0f} us, graph {t_graph * 1e6:.0f} us")
+        del pools, graph
 
     if not args.skip_extra:
         # free the big pool before the other configurations

@@ -27,12 +27,13 @@ class DevicePool:
 
 
 def make_device_pool(kv_lens, num_q_heads, num_kv_heads, head_dim, dtype="bf16", seed=0,
-                     device="cuda:0") -> DevicePool:
+                     device="cuda:0", table_seed=None) -> DevicePool:
     """One shared pool holding every request's KV; block ids are a seeded
-    permutation (random physical placement)."""
+    permutation (random physical placement).  table_seed fixes the placement
+    independently of the data (the layers of one model share a block table)."""
     import torch
     kv_lens = np.asarray(kv_lens, dtype=np.int32)
-    bt, used = wl.build_block_table(kv_lens, seed=seed)
+    bt, used = wl.build_block_table(kv_lens, seed=seed if table_seed is None else table_seed)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
