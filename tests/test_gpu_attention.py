@@ -214,3 +214,31 @@ def test_matrix_core_path_one_hot_and_mean_limits(lib):
     got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=64)
     rows = np.concatenate([pb.as_float("v_blocks")[pb.block_table[0, j]] for j in range(8)], axis=1)
     assert np.abs(got[0] - rows.astype(np.float64).mean(axis=1)).max() <= 1e-5
+
+
+def test_randomised_shapes_against_oracle(lib):
+    """Seeded random sweep over batch size, lengths, head layout, head_dim,
+    dtype, output dtype, chunking, poison and host-length use."""
+    from paper_2605_23389_amd import binding as als
+    rng = np.random.default_rng(2024)
+    for trial in range(40):
+        dtype = ["fp32", "bf16"][int(rng.integers(0, 2))]
+        D = [64, 128][int(rng.integers(0, 2))]
+        Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        G = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 16]))
+        B = int(rng.integers(1, 24))
+        hi = int(rng.choice([40, 300, 1500, 5000]))
+        lens = rng.integers(1, hi + 1, B).astype(np.int32)
+        pb = wl.make_paged_batch(lens, Hkv * G, Hkv, D, dtype=dtype, seed=1000 + trial,
+                                 spare_blocks=int(rng.integers(0, 3)),
+                                 poison=[None, "nan", "inf", "big"][int(rng.integers(0, 4))],
+                                 extra_table_cols=int(rng.integers(0, 4)))
+        chunk = int(rng.choice([0, 0, 16, 64, 208, 512, 4096]))
+        flags = int(rng.choice([0, 0, als.ATTN_NO_MFMA]))
+        out_dtype = "fp32" if dtype == "fp32" or rng.random() < 0.7 else "bf16"
+        ref = oracle_out(pb)
+        got = run_attention(lib, pb, out_dtype=out_dtype, chunk_tokens=chunk, flags=flags,
+                            host_lens=bool(rng.integers(0, 2)))
+        assert np.isfinite(got).all(), (trial, dtype, D, Hkv, G, B, chunk)
+        err = np.abs(got - ref).max()
+        assert err <= TOL[dtype], (trial, dtype, D, Hkv, G, B, chunk, flags, err)
