@@ -236,7 +236,17 @@ struct AttnArgs {
   int32_t out_bf16;
   int32_t exact_grid;  // grid == total_items * head_groups exactly
   int32_t direct;      // every request is one chunk: item i is request i, no item table
+  int32_t inline_plan; // the item table travels in the kernel arguments (InlinePlan)
   float c;             // scale * log2(e)
+};
+
+// Small launches carry their work plan in the kernel-argument segment instead
+// of having a plan kernel write it to memory first: one 32-bit word per item,
+// request index in the high and chunk index in the low 16 bits, built on the
+// host from the host copy of the lengths.  4 KiB of kernel arguments bound it.
+constexpr int kInlineItems = 960;
+struct InlinePlan {
+  uint32_t item[kInlineItems];
 };
 
 // Online-softmax state of one token group for one query head.
@@ -333,7 +343,7 @@ __device__ __forceinline__ void merge_state(HeadState<EPL>& s, float om, float o
 }
 
 template <typename T, int D, int G>
-__global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan ip) {
   constexpr int EPL = Elem<T>::kPerLoad;
   constexpr int LPT = D / EPL;
   constexpr int NLD = kBlock * D * sizeof(T) / 1024;
@@ -349,8 +359,15 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a) {
   const int h = hg / a.kv_div;                       // KV head they read
   if (!a.exact_grid && item >= a.hdr->total_items) return;
   int4 it;
-  if (a.direct) it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
-  else it = a.items[item];
+  if (a.direct) {
+    it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
+  } else if (a.inline_plan) {
+    const uint32_t w = ip.item[item];
+    const int rb = static_cast<int>(w >> 16);
+    it = make_int4(rb, static_cast<int>(w & 0xFFFFu), min(a.kv_lens[rb], a.max_blocks_per_seq * kBlock), 0);
+  } else {
+    it = a.items[item];
+  }
   const int b = it.x;
   const int kv_len = it.z;  // already cut to the block_table row
   const int Hq = a.head_groups * G;
@@ -603,7 +620,7 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
 }
 
 // G = query heads per workgroup (<= 16), D = 128, bf16.
-__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G) {
+__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, InlinePlan ip) {
   constexpr int D = 128;
   constexpr size_t kSlabBytes = static_cast<size_t>(kBlock) * D * 2;
   // the K transpose tiles (loop) and the cross-wave merge buffers (epilogue)
@@ -620,8 +637,15 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G) 
   const int h = hg / a.kv_div;
   if (!a.exact_grid && item >= a.hdr->total_items) return;
   int4 it;
-  if (a.direct) it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
-  else it = a.items[item];
+  if (a.direct) {
+    it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
+  } else if (a.inline_plan) {
+    const uint32_t w = ip.item[item];
+    const int rb = static_cast<int>(w >> 16);
+    it = make_int4(rb, static_cast<int>(w & 0xFFFFu), min(a.kv_lens[rb], a.max_blocks_per_seq * kBlock), 0);
+  } else {
+    it = a.items[item];
+  }
   const int b = it.x;
   const int kv_len = it.z;  // already cut to the block_table row
   const int Hq = a.head_groups * G;
@@ -762,8 +786,13 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G) 
 // the online softmax): with M = max_i m_i,
 //   out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i.
 // D/4 lanes per (request, query head); each lane owns 4 output dimensions.
+struct InlineFirst {
+  uint16_t first[2 * kInlineItems];  // first item of each request, batch + 1 entries
+};
+
 template <int D>
 __global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict__ cu_chunks,
+                                                      InlineFirst icu, int use_inline,
                                                       const float2* __restrict__ part_ml,
                                                       const float* __restrict__ part_acc,
                                                       char* __restrict__ out, int batch, int Hq,
@@ -774,8 +803,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict_
   if (pair >= batch * Hq) return;
   const int b = pair / Hq;
   const int hq = pair - b * Hq;
-  const int first = cu_chunks[b];
-  const int n = cu_chunks[b + 1] - first;
+  const int first = use_inline ? icu.first[b] : cu_chunks[b];
+  const int n = (use_inline ? icu.first[b + 1] : cu_chunks[b + 1]) - first;
   if (n <= 1) return;  // finished by the attention kernel itself
   float M = kNegInf;
   for (int i = 0; i < n; ++i) M = fmaxf(M, part_ml[static_cast<size_t>(first + i) * Hq + hq].x);
@@ -896,6 +925,9 @@ int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
 }
 
 struct Checked {
+  bool use_inline;       // plan travels in kernel arguments (no plan kernel)
+  InlinePlan ip;
+  InlineFirst icu;
   int chunk;
   int64_t total_tokens;  // exact when host lens are given, else worst case
   int64_t items;         // exact or upper bound
@@ -967,6 +999,22 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
     out->items = static_cast<int64_t>(p->batch) * ((cap + out->chunk - 1) / out->chunk);
   }
   out->w = layout_for(*p, out->items);
+  // small launches with known lengths: build the plan here and ship it in the
+  // kernel arguments
+  out->use_inline = false;
+  if (kv_lens_host && out->any_split && out->items <= kInlineItems && p->batch < 2 * kInlineItems) {
+    bool fits = true;
+    int64_t n = 0;
+    for (int b = 0; b < p->batch && fits; ++b) {
+      const int nch = (kv_lens_host[b] + out->chunk - 1) / out->chunk;
+      fits = nch <= 0xFFFF;
+      out->icu.first[b] = static_cast<uint16_t>(n);
+      for (int c = 0; c < nch && fits; ++c)
+        out->ip.item[n++] = (static_cast<uint32_t>(b) << 16) | static_cast<uint32_t>(c);
+    }
+    out->icu.first[p->batch] = static_cast<uint16_t>(n);
+    out->use_inline = fits && p->batch <= 0xFFFF;
+  }
   if (out->items * p->num_q_heads > 0x7FFFFFFFLL)
     return als::fail(AS_ERANGE, "%s: %lld work items exceed the launch limit", what,
                      static_cast<long long>(out->items * p->num_q_heads));
@@ -981,12 +1029,12 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
 }
 
 template <typename T, int D>
-void launch_attn(int G, dim3 grid, hipStream_t s, const AttnArgs& a) {
+void launch_attn(int G, dim3 grid, hipStream_t s, const AttnArgs& a, const InlinePlan& ip) {
   switch (G) {
-    case 1: hipLaunchKernelGGL((attn_kernel<T, D, 1>), grid, dim3(kThreads), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((attn_kernel<T, D, 2>), grid, dim3(kThreads), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((attn_kernel<T, D, 4>), grid, dim3(kThreads), 0, s, a); break;
-    default: hipLaunchKernelGGL((attn_kernel<T, D, 8>), grid, dim3(kThreads), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((attn_kernel<T, D, 1>), grid, dim3(kThreads), 0, s, a, ip); break;
+    case 2: hipLaunchKernelGGL((attn_kernel<T, D, 2>), grid, dim3(kThreads), 0, s, a, ip); break;
+    case 4: hipLaunchKernelGGL((attn_kernel<T, D, 4>), grid, dim3(kThreads), 0, s, a, ip); break;
+    default: hipLaunchKernelGGL((attn_kernel<T, D, 8>), grid, dim3(kThreads), 0, s, a, ip); break;
   }
 }
 
@@ -1012,6 +1060,7 @@ AttnArgs make_args(const as_attn_params& p, const Checked& ck, const void* q, co
   a.out_bf16 = p.out_dtype == AS_DTYPE_BF16;
   a.exact_grid = ck.exact;
   a.direct = ck.exact && !ck.any_split;
+  a.inline_plan = ck.use_inline;
   const float scale = p.scale > 0.f ? p.scale : 1.0f / std::sqrt(static_cast<float>(p.head_dim));
   a.c = scale * 1.4426950408889634f;
   return a;
@@ -1056,7 +1105,7 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
   // When the host lengths show that no request needs more than one chunk,
   // item i is request i and neither the plan nor the combine kernel runs.
   const bool direct = ck.exact && !ck.any_split;
-  if (!direct && !(p->flags & AS_ATTN_REUSE_PLAN)) {
+  if (!direct && !ck.use_inline && !(p->flags & AS_ATTN_REUSE_PLAN)) {
     st = run_plan(*p, ck, kv_lens, ws, s);
     if (st != AS_OK) return st;
   }
@@ -1076,7 +1125,7 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
     a.head_groups = p->num_q_heads / mfma_heads;
     a.kv_div = group / mfma_heads;
     const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
-    hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(kThreads), 0, s, a, mfma_heads);
+    hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
   } else {
     // query heads handled by one workgroup: the largest of 8, 4, 2, 1 that
     // divides the GQA group; a group that is not a power of two up to 8 is
@@ -1086,11 +1135,11 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
     a.kv_div = group / G;
     const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
     if (p->dtype == AS_DTYPE_BF16) {
-      if (p->head_dim == 128) launch_attn<bf16_t, 128>(G, grid, s, a);
-      else launch_attn<bf16_t, 64>(G, grid, s, a);
+      if (p->head_dim == 128) launch_attn<bf16_t, 128>(G, grid, s, a, ck.ip);
+      else launch_attn<bf16_t, 64>(G, grid, s, a, ck.ip);
     } else {
-      if (p->head_dim == 128) launch_attn<float, 128>(G, grid, s, a);
-      else launch_attn<float, 64>(G, grid, s, a);
+      if (p->head_dim == 128) launch_attn<float, 128>(G, grid, s, a, ck.ip);
+      else launch_attn<float, 64>(G, grid, s, a, ck.ip);
     }
   }
   ALS_HIP_CHECK(hipGetLastError());
@@ -1101,10 +1150,10 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
     const dim3 cgrid((pairs + pairs_per_block - 1) / pairs_per_block);
     const int32_t* cu = reinterpret_cast<const int32_t*>(ws + ck.w.cu_off);
     if (p->head_dim == 128)
-      hipLaunchKernelGGL(combine_kernel<128>, cgrid, dim3(256), 0, s, cu, a.part_ml, a.part_acc,
+      hipLaunchKernelGGL(combine_kernel<128>, cgrid, dim3(256), 0, s, cu, ck.icu, int(ck.use_inline), a.part_ml, a.part_acc,
                          a.out, p->batch, p->num_q_heads, a.out_bf16);
     else
-      hipLaunchKernelGGL(combine_kernel<64>, cgrid, dim3(256), 0, s, cu, a.part_ml, a.part_acc,
+      hipLaunchKernelGGL(combine_kernel<64>, cgrid, dim3(256), 0, s, cu, ck.icu, int(ck.use_inline), a.part_ml, a.part_acc,
                          a.out, p->batch, p->num_q_heads, a.out_bf16);
     ALS_HIP_CHECK(hipGetLastError());
   }
@@ -1123,11 +1172,13 @@ extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks
   if (st != AS_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  if (!(ck.exact && !ck.any_split) && !(p->flags & AS_ATTN_REUSE_PLAN)) {
+  // the sweep always reads its plan from the workspace (never from kernel arguments)
+  if (!(ck.exact && !ck.any_split)) {
     st = run_plan(*p, ck, kv_lens, ws, s);
     if (st != AS_OK) return st;
   }
   AttnArgs a = make_args(*p, ck, k_blocks, k_blocks, v_blocks, block_table, kv_lens, checksum, ws);
+  a.inline_plan = 0;
   const size_t esz = p->dtype == AS_DTYPE_BF16 ? 2 : 4;
   const size_t slab = static_cast<size_t>(kBlock) * p->head_dim * esz;
   const dim3 grid(static_cast<unsigned>(ck.items * p->num_kv_heads));
