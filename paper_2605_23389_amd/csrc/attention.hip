@@ -358,24 +358,31 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
   const int hg = blockIdx.x - item * a.head_groups;  // query heads hg*G .. hg*G+G-1
   const int h = hg / a.kv_div;                       // KV head they read
   if (!a.exact_grid && item >= a.hdr->total_items) return;
-  int4 it;
-  if (a.direct) {
-    it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
-  } else if (a.inline_plan) {
-    const uint32_t w = ip.item[item];
-    const int rb = static_cast<int>(w >> 16);
-    it = make_int4(rb, static_cast<int>(w & 0xFFFFu), min(a.kv_lens[rb], a.max_blocks_per_seq * kBlock), 0);
-  } else {
-    it = a.items[item];
+  // (request, chunk) of this item.  The block ids of the chunk are requested
+  // before the length is known (index clamped into the table row), so that the
+  // length and the ids arrive together instead of one after the other.
+  int4 it = make_int4(item, 0, 0, 0);
+  if (!a.direct) {
+    if (a.inline_plan) {
+      const uint32_t w = ip.item[item];
+      it.x = static_cast<int>(w >> 16);
+      it.y = static_cast<int>(w & 0xFFFFu);
+    } else {
+      it = a.items[item];
+    }
   }
   const int b = it.x;
-  const int kv_len = it.z;  // already cut to the block_table row
-  const int Hq = a.head_groups * G;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-
   const int t0 = it.y * a.chunk;
+  // lane i holds the id of tile wave + 4*i of the chunk
+  int my_id = a.block_table[static_cast<size_t>(b) * a.max_blocks_per_seq +
+                            min(t0 / kBlock + wave + kWaves * lane, a.max_blocks_per_seq - 1)];
+  my_id = min(max(my_id, 0), a.num_blocks - 1);
+  const int kv_len = (a.direct || a.inline_plan) ? min(a.kv_lens[b], a.max_blocks_per_seq * kBlock)
+                                                 : it.z;  // cut to the block_table row
+  const int Hq = a.head_groups * G;
   const int ntok = min(kv_len - t0, a.chunk);
   if (ntok <= 0) {  // kv_len <= 0: defined result is zeros
     for (int i = tid; i < G * D; i += kThreads) {
@@ -388,13 +395,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
   const int ntiles = (ntok + kBlock - 1) / kBlock;
   const bool single = kv_len <= a.chunk;
 
-  // block ids of this wave's tiles: lane i holds the id of tile wave + 4*i
   const int my_tiles = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
-  int my_id = 0;
-  if (lane < my_tiles) {
-    my_id = a.block_table[static_cast<size_t>(b) * a.max_blocks_per_seq + t0 / kBlock + wave + kWaves * lane];
-    my_id = min(max(my_id, 0), a.num_blocks - 1);
-  }
 
   u32x4 qr[G];
 #pragma unroll
@@ -636,26 +637,33 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   const int hg = blockIdx.x - item * a.head_groups;
   const int h = hg / a.kv_div;
   if (!a.exact_grid && item >= a.hdr->total_items) return;
-  int4 it;
-  if (a.direct) {
-    it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
-  } else if (a.inline_plan) {
-    const uint32_t w = ip.item[item];
-    const int rb = static_cast<int>(w >> 16);
-    it = make_int4(rb, static_cast<int>(w & 0xFFFFu), min(a.kv_lens[rb], a.max_blocks_per_seq * kBlock), 0);
-  } else {
-    it = a.items[item];
+  // (request, chunk) of this item.  The block ids of the chunk are requested
+  // before the length is known (index clamped into the table row), so that the
+  // length and the ids arrive together instead of one after the other.
+  int4 it = make_int4(item, 0, 0, 0);
+  if (!a.direct) {
+    if (a.inline_plan) {
+      const uint32_t w = ip.item[item];
+      it.x = static_cast<int>(w >> 16);
+      it.y = static_cast<int>(w & 0xFFFFu);
+    } else {
+      it = a.items[item];
+    }
   }
   const int b = it.x;
-  const int kv_len = it.z;  // already cut to the block_table row
-  const int Hq = a.head_groups * G;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int t0 = it.y * a.chunk;
+  // lane i holds the id of tile wave + 4*i of the chunk
+  int my_id = a.block_table[static_cast<size_t>(b) * a.max_blocks_per_seq +
+                            min(t0 / kBlock + wave + kWaves * lane, a.max_blocks_per_seq - 1)];
+  my_id = min(max(my_id, 0), a.num_blocks - 1);
+  const int kv_len = (a.direct || a.inline_plan) ? min(a.kv_lens[b], a.max_blocks_per_seq * kBlock)
+                                                 : it.z;  // cut to the block_table row
+  const int Hq = a.head_groups * G;
   const int col = lane & 15;
   const int rg = lane >> 4;
-
-  const int t0 = it.y * a.chunk;
   const int ntok = min(kv_len - t0, a.chunk);
   if (ntok <= 0) {
     for (int i = tid; i < G * D; i += kThreads) {
@@ -668,11 +676,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   const int ntiles = (ntok + kBlock - 1) / kBlock;
   const bool single = kv_len <= a.chunk;
   const int my_tiles = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
-  int my_id = 0;
-  if (lane < my_tiles) {
-    my_id = a.block_table[static_cast<size_t>(b) * a.max_blocks_per_seq + t0 / kBlock + wave + kWaves * lane];
-    my_id = min(max(my_id, 0), a.num_blocks - 1);
-  }
 
   // Q^T operand: head `col`, dims 8*(4j+rg) .. +8 for MFMA j; zero past G
   bf16x8_t qb[4];
