@@ -18,7 +18,7 @@
  * Paged KV layout (the library's contract; the paper only speaks of "memory
  * blocks", Section 3.3):
  *   k_blocks, v_blocks : [num_blocks][num_kv_heads][block_size][head_dim]
- *                        row-major, block_size == 16, fp32 or bf16;
+ *                        row-major, block_size == 16, fp32, bf16 or fp16;
  *   block_table        : int32 [batch][max_blocks_per_seq];
  *   logical token t of request b is row t % 16 of physical block
  *   block_table[b][t / 16].  Rows at or past kv_lens[b] in a request's last
@@ -46,6 +46,7 @@ typedef enum {
 
 #define AS_DTYPE_F32 0
 #define AS_DTYPE_BF16 1
+#define AS_DTYPE_F16 2 /* IEEE binary16: the precision the paper runs its models in (Section 4.1) */
 
 /* Library version (major*10000 + minor*100 + patch). */
 int32_t as_version(void);
@@ -131,7 +132,8 @@ as_status as_dfs_batches(const int32_t* kv_lens, const int32_t* blocks, int32_t 
  * for the newest token's query of every request b against all kv_lens[b]
  * cached keys / values of that request (the newest token's own k, v are
  * already in the cache; there is no causal mask).  Query head h reads KV head
- * h / (num_q_heads / num_kv_heads).  Accumulation is fp32.
+ * h / (num_q_heads / num_kv_heads).  Accumulation is fp32 for every input
+ * type; 16-bit inputs are widened exactly.
  * -------------------------------------------------------------------------- */
 typedef struct {
   int32_t dtype;              /* AS_DTYPE_* of q, k_blocks, v_blocks                */

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(HERE, "libalignedserve.so")
 AS_OK, AS_EINVAL, AS_ERANGE, AS_EWORKSPACE, AS_EUNSUPPORTED, AS_EHIP = range(6)
 STATUS_NAMES = {0: "AS_OK", 1: "AS_EINVAL", 2: "AS_ERANGE", 3: "AS_EWORKSPACE",
                 4: "AS_EUNSUPPORTED", 5: "AS_EHIP"}
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 ATTN_REUSE_PLAN, ATTN_NO_MFMA = 1, 2
 
 EXPORTS = [
@@ -177,6 +177,8 @@ def _torch_dtype_code(t) -> int:
         return DTYPE_F32
     if t.dtype == torch.bfloat16:
         return DTYPE_BF16
+    if t.dtype == torch.float16:
+        return DTYPE_F16
     raise AlignedServeError(AS_EUNSUPPORTED, f"tensor dtype {t.dtype}")
 
 

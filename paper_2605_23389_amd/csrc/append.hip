@@ -53,9 +53,9 @@ extern "C" as_status as_kv_append(const void* k_new, const void* v_new, void* k_
   if (p->batch < 1 || p->num_kv_heads < 1 || p->num_blocks < 1 || p->max_blocks_per_seq < 1)
     return als::fail(AS_EINVAL, "as_kv_append: batch, num_kv_heads, num_blocks, max_blocks_per_seq must be positive");
   if (p->block_size != 16) return als::fail(AS_EUNSUPPORTED, "as_kv_append: block_size %d (only 16 is built)", p->block_size);
-  if (p->dtype != AS_DTYPE_F32 && p->dtype != AS_DTYPE_BF16)
+  if (p->dtype < AS_DTYPE_F32 || p->dtype > AS_DTYPE_F16)
     return als::fail(AS_EUNSUPPORTED, "as_kv_append: dtype %d", p->dtype);
-  const int esz = p->dtype == AS_DTYPE_BF16 ? 2 : 4;
+  const int esz = p->dtype == AS_DTYPE_F32 ? 4 : 2;
   const int row_bytes = p->head_dim * esz;
   if (p->head_dim < 1 || row_bytes % 16)
     return als::fail(AS_EUNSUPPORTED, "as_kv_append: head_dim %d rows are not a multiple of 16 bytes", p->head_dim);

@@ -51,10 +51,16 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 struct bf16_t { uint16_t bits; };
+struct f16_t { uint16_t bits; };
+typedef _Float16 h16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 h16x4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 h16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
 
 template <typename T> struct Elem;
 template <> struct Elem<float> { static constexpr int kPerLoad = 4; };
 template <> struct Elem<bf16_t> { static constexpr int kPerLoad = 8; };
+template <> struct Elem<f16_t> { static constexpr int kPerLoad = 8; };
 
 // ------------------------------------------------------------------ workspace
 // [0,256)            PlanHeader
@@ -165,6 +171,21 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return static_cast<uint16_t>(u >> 16);
 }
 
+__device__ __forceinline__ uint16_t f32_to_f16_rne(float f) {
+  const _Float16 h = static_cast<_Float16>(f);  // v_cvt_f16_f32, round to nearest even
+  return __builtin_bit_cast(uint16_t, h);
+}
+
+// out_dtype: 0 fp32, 1 bf16, 2 fp16
+__device__ __forceinline__ uint16_t f32_to_out16(float f, int out_dtype) {
+  return out_dtype == AS_DTYPE_BF16 ? f32_to_bf16_rne(f) : f32_to_f16_rne(f);
+}
+
+__device__ __forceinline__ void store_out(char* out, size_t idx, float v, int out_dtype) {
+  if (out_dtype == AS_DTYPE_F32) reinterpret_cast<float*>(out)[idx] = v;
+  else reinterpret_cast<uint16_t*>(out)[idx] = f32_to_out16(v, out_dtype);
+}
+
 // dot of the EPL elements a lane holds of one key row with its slice of q
 template <typename T> struct Dot;
 template <> struct Dot<float> {
@@ -197,6 +218,20 @@ template <> struct Dot<bf16_t> {
   }
 };
 
+template <> struct Dot<f16_t> {
+  // v_dot2c_f32_f16: two fp16 products accumulated into an fp32 register
+  __device__ static __forceinline__ float run(const u32x4& ku, const u32x4& qu) {
+    const h16x8_t k = __builtin_bit_cast(h16x8_t, ku);
+    const h16x8_t q = __builtin_bit_cast(h16x8_t, qu);
+    float s = 0.f;
+    s = __builtin_amdgcn_fdot2(__builtin_shufflevector(k, k, 0, 1), __builtin_shufflevector(q, q, 0, 1), s, false);
+    s = __builtin_amdgcn_fdot2(__builtin_shufflevector(k, k, 2, 3), __builtin_shufflevector(q, q, 2, 3), s, false);
+    s = __builtin_amdgcn_fdot2(__builtin_shufflevector(k, k, 4, 5), __builtin_shufflevector(q, q, 4, 5), s, false);
+    s = __builtin_amdgcn_fdot2(__builtin_shufflevector(k, k, 6, 7), __builtin_shufflevector(q, q, 6, 7), s, false);
+    return s;
+  }
+};
+
 // widen the EPL elements of one loaded 128-bit word to fp32
 template <typename T> struct Widen;
 template <> struct Widen<float> {
@@ -209,6 +244,14 @@ template <> struct Widen<bf16_t> {
   __device__ static __forceinline__ void run(const u32x4& v, float (&o)[8]) {
     o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x); o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
     o[4] = bf16_lo(v.z); o[5] = bf16_hi(v.z); o[6] = bf16_lo(v.w); o[7] = bf16_hi(v.w);
+  }
+};
+
+template <> struct Widen<f16_t> {
+  __device__ static __forceinline__ void run(const u32x4& vu, float (&o)[8]) {
+    const f32x8 w = __builtin_convertvector(__builtin_bit_cast(h16x8_t, vu), f32x8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = w[e];
   }
 };
 
@@ -233,7 +276,7 @@ struct AttnArgs {
   int32_t num_blocks;
   int32_t max_blocks_per_seq;
   int32_t chunk;
-  int32_t out_bf16;
+  int32_t out_dtype;   // AS_DTYPE_* of out
   int32_t exact_grid;  // grid == total_items * head_groups exactly
   int32_t direct;      // every request is one chunk: item i is request i, no item table
   int32_t inline_plan; // the item table travels in the kernel arguments (InlinePlan)
@@ -387,8 +430,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
   if (ntok <= 0) {  // kv_len <= 0: defined result is zeros
     for (int i = tid; i < G * D; i += kThreads) {
       const size_t o = (static_cast<size_t>(b) * Hq + hg * G) * D + i;
-      if (a.out_bf16) reinterpret_cast<uint16_t*>(a.out)[o] = 0;
-      else reinterpret_cast<float*>(a.out)[o] = 0.f;
+      store_out(a.out, o, 0.f, a.out_dtype);
     }
     return;
   }
@@ -498,8 +540,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
     if (single) {
       const float o = acc / l;
       const size_t oi = (static_cast<size_t>(b) * Hq + hq) * D + d;
-      if (a.out_bf16) reinterpret_cast<uint16_t*>(a.out)[oi] = f32_to_bf16_rne(o);
-      else reinterpret_cast<float*>(a.out)[oi] = o;
+      store_out(a.out, oi, o, a.out_dtype);
     } else {
       const size_t pi = static_cast<size_t>(item) * Hq + hq;
       a.part_acc[pi * D + d] = acc;
@@ -509,7 +550,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
 }
 
 // ------------------------------------------------------------------ MFMA path
-// Grouped-query attention (G query heads share one KV head), bf16, D = 128.
+// Grouped-query attention (G query heads share one KV head), bf16 or fp16,
+// D = 128.
 // With G >= 4 the vector-ALU kernel above is bound by its own arithmetic (each
 // K/V element is used G times), so the two contractions move to the matrix
 // cores; the K/V stream, the work split and the merge stay as they are.
@@ -531,22 +573,60 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
 //  * The result S^T has the head on c and tokens on (r, i): a lane owns ONE
 //    head, so the online softmax costs the same for any G <= 16.
 //  * P^T (B operand of the second MFMA) is exactly what the lane computed:
-//    probabilities of its 4 tokens for head c, rounded to bf16.
+//    probabilities of its 4 tokens for head c, rounded to the element type.
 //  * V needs no LDS: the lane's four loads hold, for each of its 8 dimensions,
 //    the 4 tokens (4i+r) -- the A operand (row = dimension 8c+e, 4 contraction
 //    values) once the 16-bit halves are gathered with v_perm.  Output register
 //    i of accumulator e is dimension 32r+8i+e of head c: the lane that owns a
 //    head's softmax state also owns that head's outputs, so rescaling is
 //    lane-local.
-// The sum l is accumulated from the bf16-rounded probabilities, so numerator
-// and denominator use the same weights.
+// The sum l is accumulated from the rounded probabilities, so numerator and
+// denominator use the same weights.
 constexpr int kLdsRow = 272;                    // 256 B of a K row + 16 B pad
 constexpr int kLdsKTile = kBlock * kLdsRow;     // per wave
 constexpr int kMfmaHeads = 16;
 
-template <bool MASKED>
+// The two 16-bit element types differ only in the MFMA opcodes and in how the
+// probabilities are rounded to the element type and widened back.
+template <typename T> struct Mfma;
+template <> struct Mfma<bf16_t> {
+  __device__ static __forceinline__ f32x4 qk(const u32x4& k, const u32x4& q, const f32x4& s) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, k),
+                                                   __builtin_bit_cast(bf16x8_t, q), s, 0, 0, 0);
+  }
+  __device__ static __forceinline__ f32x4 pv(const u32x2& v, const u32x2& p, const f32x4& o) {
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, v),
+                                                     __builtin_bit_cast(s16x4, p), o, 0, 0, 0);
+  }
+  // two probabilities rounded to the element type (round to nearest even), packed
+  __device__ static __forceinline__ uint32_t pack(float a, float b) {
+    const f32x2 f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+  }
+  __device__ static __forceinline__ float pair_sum(uint32_t w) { return bf16_lo(w) + bf16_hi(w); }
+};
+template <> struct Mfma<f16_t> {
+  __device__ static __forceinline__ f32x4 qk(const u32x4& k, const u32x4& q, const f32x4& s) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h16x8_t, k),
+                                                  __builtin_bit_cast(h16x8_t, q), s, 0, 0, 0);
+  }
+  __device__ static __forceinline__ f32x4 pv(const u32x2& v, const u32x2& p, const f32x4& o) {
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(h16x4_t, v),
+                                                 __builtin_bit_cast(h16x4_t, p), o, 0, 0, 0);
+  }
+  __device__ static __forceinline__ uint32_t pack(float a, float b) {
+    const f32x2 f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, h16x2_t));
+  }
+  __device__ static __forceinline__ float pair_sum(uint32_t w) {
+    const f32x2 f = __builtin_convertvector(__builtin_bit_cast(h16x2_t, w), f32x2);
+    return f.x + f.y;
+  }
+};
+
+template <typename T, bool MASKED>
 __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr)[4],
-                                          const bf16x8_t (&qb)[4], char* lds, f32x4 (&acc)[8],
+                                          const u32x4 (&qb)[4], char* lds, f32x4 (&acc)[8],
                                           float& m_run, float& l_run, float c, int first_token,
                                           int kv_len, int lane) {
   const int col = lane & 15;
@@ -560,7 +640,7 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const u32x4 ku = *reinterpret_cast<const u32x4*>(lds + col * kLdsRow + (4 * j + rg) * 16);
-    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ku), qb[j], s, 0, 0, 0);
+    s = Mfma<T>::qk(ku, qb[j], s);
   }
   __builtin_amdgcn_wave_barrier();
 
@@ -583,20 +663,16 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
     p[i] = fast_exp2(fmaf(sv[i], c, nref));
     if (MASKED) p[i] = valid[i] ? p[i] : 0.f;
   }
-  const f32x2 p01 = {p[0], p[1]}, p23 = {p[2], p[3]};
-  const bf16x2_t b01 = __builtin_convertvector(p01, bf16x2_t);
-  const bf16x2_t b23 = __builtin_convertvector(p23, bf16x2_t);
-  const uint32_t w01 = __builtin_bit_cast(uint32_t, b01);
-  const uint32_t w23 = __builtin_bit_cast(uint32_t, b23);
-  const float psum = (bf16_lo(w01) + bf16_hi(w01)) + (bf16_lo(w23) + bf16_hi(w23));
+  const uint32_t w01 = Mfma<T>::pack(p[0], p[1]);
+  const uint32_t w23 = Mfma<T>::pack(p[2], p[3]);
+  const float psum = Mfma<T>::pair_sum(w01) + Mfma<T>::pair_sum(w23);
   l_run = fmaf(l_run, alpha, psum);
   m_run = m_new;
   if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] *= alpha;
   }
-  const u32x2 pw = {w01, w23};
-  const s16x4 pB = __builtin_bit_cast(s16x4, pw);
+  const u32x2 pB = {w01, w23};
 
   // V: gather the 16-bit halves of the 4 tokens for each of the lane's 8 dims
   u32x4 v0 = vr[0], v1 = vr[1], v2 = vr[2], v3 = vr[3];
@@ -615,12 +691,13 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
                       __builtin_amdgcn_perm(a3[w], a2[w], 0x05040100u)};
     const u32x2 hi = {__builtin_amdgcn_perm(a1[w], a0[w], 0x07060302u),
                       __builtin_amdgcn_perm(a3[w], a2[w], 0x07060302u)};
-    acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, lo), pB, acc[2 * w], 0, 0, 0);
-    acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, hi), pB, acc[2 * w + 1], 0, 0, 0);
+    acc[2 * w] = Mfma<T>::pv(lo, pB, acc[2 * w]);
+    acc[2 * w + 1] = Mfma<T>::pv(hi, pB, acc[2 * w + 1]);
   }
 }
 
-// G = query heads per workgroup (<= 16), D = 128, bf16.
+// G = query heads per workgroup (<= 16), D = 128, T = bf16_t or f16_t.
+template <typename T>
 __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, InlinePlan ip) {
   constexpr int D = 128;
   constexpr size_t kSlabBytes = static_cast<size_t>(kBlock) * D * 2;
@@ -668,8 +745,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   if (ntok <= 0) {
     for (int i = tid; i < G * D; i += kThreads) {
       const size_t o = (static_cast<size_t>(b) * Hq + hg * G) * D + i;
-      if (a.out_bf16) reinterpret_cast<uint16_t*>(a.out)[o] = 0;
-      else reinterpret_cast<float*>(a.out)[o] = 0.f;
+      store_out(a.out, o, 0.f, a.out_dtype);
     }
     return;
   }
@@ -678,7 +754,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   const int my_tiles = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
 
   // Q^T operand: head `col`, dims 8*(4j+rg) .. +8 for MFMA j; zero past G
-  bf16x8_t qb[4];
+  u32x4 qb[4];
   {
     const u32x4 zero = {0u, 0u, 0u, 0u};
     const char* qrow = a.q + (static_cast<size_t>(b) * Hq + hg * G + (col < G ? col : 0)) * D * 2;
@@ -686,7 +762,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
     for (int j = 0; j < 4; ++j) {
       u32x4 w = *reinterpret_cast<const u32x4*>(qrow + (4 * j + rg) * 16);
       w = col < G ? w : zero;
-      qb[j] = __builtin_bit_cast(bf16x8_t, w);
+      qb[j] = w;
     }
   }
 
@@ -705,8 +781,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   };
   if (my_tiles > 0) {
     const size_t off = tile_off(0);
-    load_tile<bf16_t, D>(kA, a.k_blocks + off, lane);
-    load_tile<bf16_t, D>(vA, a.v_blocks + off, lane);
+    load_tile<T, D>(kA, a.k_blocks + off, lane);
+    load_tile<T, D>(vA, a.v_blocks + off, lane);
   }
   // Only the chunk's last tile can be partial.  The hot loop takes pairs of
   // full tiles with the unmasked code; at most two tiles are left for the
@@ -717,27 +793,27 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   for (; i + 2 <= full_tiles; i += 2) {
     {
       const size_t off = tile_off(i + 1);
-      load_tile<bf16_t, D>(kB, a.k_blocks + off, lane);
-      load_tile<bf16_t, D>(vB, a.v_blocks + off, lane);
+      load_tile<T, D>(kB, a.k_blocks + off, lane);
+      load_tile<T, D>(vB, a.v_blocks + off, lane);
     }
-    mfma_tile<false>(kA, vA, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
+    mfma_tile<T, false>(kA, vA, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
     if (i + 2 < my_tiles) {
       const size_t off = tile_off(i + 2);
-      load_tile<bf16_t, D>(kA, a.k_blocks + off, lane);
-      load_tile<bf16_t, D>(vA, a.v_blocks + off, lane);
+      load_tile<T, D>(kA, a.k_blocks + off, lane);
+      load_tile<T, D>(vA, a.v_blocks + off, lane);
     }
-    mfma_tile<false>(kB, vB, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
+    mfma_tile<T, false>(kB, vB, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
   }
   if (i < my_tiles) {
     const bool haveB = i + 1 < my_tiles;
     if (haveB) {
       const size_t off = tile_off(i + 1);
-      load_tile<bf16_t, D>(kB, a.k_blocks + off, lane);
-      load_tile<bf16_t, D>(vB, a.v_blocks + off, lane);
+      load_tile<T, D>(kB, a.k_blocks + off, lane);
+      load_tile<T, D>(vB, a.v_blocks + off, lane);
     }
-    mfma_tile<true>(kA, vA, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * i) * kBlock, kv_len, lane);
+    mfma_tile<T, true>(kA, vA, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * i) * kBlock, kv_len, lane);
     if (haveB)
-      mfma_tile<true>(kB, vB, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * (i + 1)) * kBlock, kv_len, lane);
+      mfma_tile<T, true>(kB, vB, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * (i + 1)) * kBlock, kv_len, lane);
   }
 
   // each row group summed its own 4 tokens per tile; m is already common
@@ -774,8 +850,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
     if (single) {
       const float r = o / l;
       const size_t oi = (static_cast<size_t>(b) * Hq + hq) * D + d;
-      if (a.out_bf16) reinterpret_cast<uint16_t*>(a.out)[oi] = f32_to_bf16_rne(r);
-      else reinterpret_cast<float*>(a.out)[oi] = r;
+      store_out(a.out, oi, r, a.out_dtype);
     } else {
       const size_t pi = static_cast<size_t>(item) * Hq + hq;
       a.part_acc[pi * D + d] = o;
@@ -799,7 +874,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict_
                                                       const float2* __restrict__ part_ml,
                                                       const float* __restrict__ part_acc,
                                                       char* __restrict__ out, int batch, int Hq,
-                                                      int out_bf16) {
+                                                      int out_dtype) {
   constexpr int LPP = D / 4;
   const int pair = blockIdx.x * (256 / LPP) + threadIdx.x / LPP;
   const int sub = threadIdx.x % LPP;
@@ -825,10 +900,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict_
   const float inv = 1.f / l;
   const size_t oi = (static_cast<size_t>(b) * Hq + hq) * D + sub * 4;
   const float o0 = acc.x * inv, o1 = acc.y * inv, o2 = acc.z * inv, o3 = acc.w * inv;
-  if (out_bf16) {
+  if (out_dtype != AS_DTYPE_F32) {
     uint2 w;
-    w.x = f32_to_bf16_rne(o0) | (static_cast<uint32_t>(f32_to_bf16_rne(o1)) << 16);
-    w.y = f32_to_bf16_rne(o2) | (static_cast<uint32_t>(f32_to_bf16_rne(o3)) << 16);
+    w.x = f32_to_out16(o0, out_dtype) | (static_cast<uint32_t>(f32_to_out16(o1, out_dtype)) << 16);
+    w.y = f32_to_out16(o2, out_dtype) | (static_cast<uint32_t>(f32_to_out16(o3, out_dtype)) << 16);
     *reinterpret_cast<uint2*>(out + oi * 2) = w;
   } else {
     *reinterpret_cast<float4*>(out + oi * 4) = make_float4(o0, o1, o2, o3);
@@ -919,7 +994,7 @@ int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
   // the grouped-query (matrix-core) kernel merges and writes up to 16 heads
   // per item: its per-item overhead is about 4x, so its best chunk about 2x
   const int group = p.num_q_heads / p.num_kv_heads;
-  const bool wide = p.dtype == AS_DTYPE_BF16 && p.head_dim == 128 && group >= 4;
+  const bool wide = p.dtype != AS_DTYPE_F32 && p.head_dim == 128 && group >= 4;
   int chunk = static_cast<int>(std::sqrt(wide ? t : t / 4.0));
   chunk = (chunk + 63) / 64 * 64;
   if (chunk < 256) chunk = 256;
@@ -952,8 +1027,8 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
     return als::fail(AS_EUNSUPPORTED, "%s: block_size %d (only 16 is built)", what, p->block_size);
   if (p->head_dim != 64 && p->head_dim != 128)
     return als::fail(AS_EUNSUPPORTED, "%s: head_dim %d (64 and 128 are built)", what, p->head_dim);
-  if ((p->dtype != AS_DTYPE_F32 && p->dtype != AS_DTYPE_BF16) ||
-      (p->out_dtype != AS_DTYPE_F32 && p->out_dtype != AS_DTYPE_BF16))
+  if (p->dtype < AS_DTYPE_F32 || p->dtype > AS_DTYPE_F16 || p->out_dtype < AS_DTYPE_F32 ||
+      p->out_dtype > AS_DTYPE_F16)
     return als::fail(AS_EUNSUPPORTED, "%s: dtype %d / out_dtype %d", what, p->dtype, p->out_dtype);
   if (!(p->scale >= 0.f) || std::isinf(p->scale))
     return als::fail(AS_EINVAL, "%s: scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))", what);
@@ -1060,7 +1135,7 @@ AttnArgs make_args(const as_attn_params& p, const Checked& ck, const void* q, co
   a.num_blocks = p.num_blocks;
   a.max_blocks_per_seq = p.max_blocks_per_seq;
   a.chunk = ck.chunk;
-  a.out_bf16 = p.out_dtype == AS_DTYPE_BF16;
+  a.out_dtype = p.out_dtype;
   a.exact_grid = ck.exact;
   a.direct = ck.exact && !ck.any_split;
   a.inline_plan = ck.use_inline;
@@ -1115,11 +1190,11 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
   AttnArgs a = make_args(*p, ck, q, k_blocks, v_blocks, block_table, kv_lens, out, ws);
 
   const int group = p->num_q_heads / p->num_kv_heads;
-  // Matrix-core path: bf16, D = 128, grouped-query shapes where the vector-ALU
+  // Matrix-core path: 16-bit inputs, D = 128, grouped-query shapes where the vector-ALU
   // kernel is bound by its own arithmetic.  One workgroup takes up to 16 heads
   // of a group; wider groups are cut into 16s or 8s.
   int mfma_heads = 0;
-  if (p->dtype == AS_DTYPE_BF16 && p->head_dim == 128 && group >= 4 && !(p->flags & AS_ATTN_NO_MFMA)) {
+  if (p->dtype != AS_DTYPE_F32 && p->head_dim == 128 && group >= 4 && !(p->flags & AS_ATTN_NO_MFMA)) {
     if (group <= 16) mfma_heads = group;
     else if (group % 16 == 0) mfma_heads = 16;
     else if (group % 8 == 0) mfma_heads = 8;
@@ -1128,7 +1203,10 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
     a.head_groups = p->num_q_heads / mfma_heads;
     a.kv_div = group / mfma_heads;
     const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
-    hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+    if (p->dtype == AS_DTYPE_BF16)
+      hipLaunchKernelGGL(attn_mfma_kernel<bf16_t>, grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+    else
+      hipLaunchKernelGGL(attn_mfma_kernel<f16_t>, grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
   } else {
     // query heads handled by one workgroup: the largest of 8, 4, 2, 1 that
     // divides the GQA group; a group that is not a power of two up to 8 is
@@ -1140,6 +1218,9 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
     if (p->dtype == AS_DTYPE_BF16) {
       if (p->head_dim == 128) launch_attn<bf16_t, 128>(G, grid, s, a, ck.ip);
       else launch_attn<bf16_t, 64>(G, grid, s, a, ck.ip);
+    } else if (p->dtype == AS_DTYPE_F16) {
+      if (p->head_dim == 128) launch_attn<f16_t, 128>(G, grid, s, a, ck.ip);
+      else launch_attn<f16_t, 64>(G, grid, s, a, ck.ip);
     } else {
       if (p->head_dim == 128) launch_attn<float, 128>(G, grid, s, a, ck.ip);
       else launch_attn<float, 64>(G, grid, s, a, ck.ip);
@@ -1154,10 +1235,10 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
     const int32_t* cu = reinterpret_cast<const int32_t*>(ws + ck.w.cu_off);
     if (p->head_dim == 128)
       hipLaunchKernelGGL(combine_kernel<128>, cgrid, dim3(256), 0, s, cu, ck.icu, int(ck.use_inline), a.part_ml, a.part_acc,
-                         a.out, p->batch, p->num_q_heads, a.out_bf16);
+                         a.out, p->batch, p->num_q_heads, a.out_dtype);
     else
       hipLaunchKernelGGL(combine_kernel<64>, cgrid, dim3(256), 0, s, cu, ck.icu, int(ck.use_inline), a.part_ml, a.part_acc,
-                         a.out, p->batch, p->num_q_heads, a.out_bf16);
+                         a.out, p->batch, p->num_q_heads, a.out_dtype);
     ALS_HIP_CHECK(hipGetLastError());
   }
   return AS_OK;
@@ -1182,7 +1263,7 @@ extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks
   }
   AttnArgs a = make_args(*p, ck, k_blocks, k_blocks, v_blocks, block_table, kv_lens, checksum, ws);
   a.inline_plan = 0;
-  const size_t esz = p->dtype == AS_DTYPE_BF16 ? 2 : 4;
+  const size_t esz = p->dtype == AS_DTYPE_F32 ? 4 : 2;
   const size_t slab = static_cast<size_t>(kBlock) * p->head_dim * esz;
   const dim3 grid(static_cast<unsigned>(ck.items * p->num_kv_heads));
   switch (slab / 1024) {

@@ -34,7 +34,7 @@ def make_device_pool(kv_lens, num_q_heads, num_kv_heads, head_dim, dtype="bf16",
     import torch
     kv_lens = np.asarray(kv_lens, dtype=np.int32)
     bt, used = wl.build_block_table(kv_lens, seed=seed if table_seed is None else table_seed)
-    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    tdt = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}[dtype]
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
     shape = (used, num_kv_heads, wl.BLOCK_SIZE, head_dim)

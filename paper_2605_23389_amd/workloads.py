@@ -17,7 +17,7 @@ Layout of the paged pool (the library's contract):
     block_table        : int32 [batch][max_blocks_per_seq]
     kv_lens            : int32 [batch]
 Logical token t of request b lives in physical block block_table[b, t // bs],
-row t % bs.  bf16 tensors are carried in NumPy as uint16 bit patterns.
+row t % bs.  bf16 and fp16 tensors are carried in NumPy as uint16 bit patterns.
 """
 from __future__ import annotations
 
@@ -52,6 +52,21 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     """Exact widening of bf16 bit patterns (uint16) to fp32."""
     b = np.ascontiguousarray(b, dtype=np.uint16)
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to IEEE binary16 (round-to-nearest-even), as uint16 bits."""
+    with np.errstate(over="ignore"):
+        return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Exact widening of binary16 bit patterns (uint16) to fp32."""
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+_TO_BITS = {"bf16": f32_to_bf16_bits, "fp16": f32_to_f16_bits}
+_FROM_BITS = {"bf16": bf16_bits_to_f32, "fp16": f16_bits_to_f32}
 
 
 # ----------------------------------------------------------------------------
@@ -90,7 +105,7 @@ class PagedBatch:
     """One decode-iteration attention problem over a paged KV pool.
 
     q, k_blocks, v_blocks are float32 arrays when dtype == "fp32" and uint16
-    bf16 bit patterns when dtype == "bf16".
+    bit patterns when dtype is "bf16" or "fp16".
     """
     dtype: str
     q: np.ndarray            # [B][H_q][D]
@@ -115,12 +130,12 @@ class PagedBatch:
     def as_float(self, name: str) -> np.ndarray:
         """q / k_blocks / v_blocks widened to a float array (exact)."""
         a = getattr(self, name)
-        return bf16_bits_to_f32(a) if self.dtype == "bf16" else a
+        return _FROM_BITS[self.dtype](a) if self.dtype in _FROM_BITS else a
 
 
 def _draw_tensor(rng, shape, dtype):
     x = rng.standard_normal(shape, dtype=np.float32)
-    return f32_to_bf16_bits(x) if dtype == "bf16" else x
+    return _TO_BITS[dtype](x) if dtype in _TO_BITS else x
 
 
 def poison_value(dtype: str, kind: str):
@@ -128,7 +143,7 @@ def poison_value(dtype: str, kind: str):
     table = {"nan": np.float32(np.nan), "inf": np.float32(np.inf),
              "ninf": np.float32(-np.inf), "big": np.float32(1e30), "zero": np.float32(0)}
     v = np.asarray([table[kind]], dtype=np.float32)
-    return f32_to_bf16_bits(v)[0] if dtype == "bf16" else v[0]
+    return _TO_BITS[dtype](v)[0] if dtype in _TO_BITS else v[0]
 
 
 def make_paged_batch(kv_lens, num_q_heads: int, num_kv_heads: int, head_dim: int,

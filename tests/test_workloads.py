@@ -62,3 +62,20 @@ def test_random_grouping_and_block_table():
     assert used == 4 and bt.shape == (3, 2)
     ids = [bt[0, 0], bt[1, 0], bt[1, 1], bt[2, 0]]
     assert len(set(ids)) == 4 and max(ids) < 10
+
+
+def test_fp16_bits_round_to_nearest_even_and_widen_exactly():
+    # 1 + 2^-11 is a tie between 1 and 1 + 2^-10: goes to the even mantissa (1.0);
+    # 1 + 3*2^-11 is a tie that goes up to 1 + 2^-9
+    x = np.float32([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, -2.5, 65520.0, 6e-8])
+    b = wl.f32_to_f16_bits(x)
+    assert b.dtype == np.uint16
+    assert b[0] == 0x3C00 and b[1] == 0x3C02 and b[2] == 0xC100
+    assert b[3] == 0x7C00            # rounds to +inf (largest finite is 65504)
+    assert b[4] == 0x0001            # smallest subnormal, 2^-24
+    back = wl.f16_bits_to_f32(b[:3])
+    assert back.tolist() == [1.0, 1.0 + 2.0 ** -9, -2.5]
+    pb = wl.make_paged_batch(np.array([5, 20], dtype=np.int32), 4, 2, 8, dtype="fp16", seed=1)
+    assert pb.q.dtype == np.uint16
+    q = pb.as_float("q")
+    assert np.array_equal(wl.f32_to_f16_bits(q), pb.q)      # already representable
