@@ -319,10 +319,11 @@ as_status as_pipeline_destroy(as_pipeline* p);
  * same arguments would read (same block table, same lengths, same work
  * split) and folds them into a checksum, with no other arithmetic.  Its
  * bandwidth is the ceiling the attention kernel is compared with.
- * checksum: device uint32[256], XOR-accumulated with atomics (slot = workgroup
- * index mod 256); the XOR of the 256 slots equals the XOR of every 32-bit
- * word of every K and V block the batch references (whole blocks), for the
- * slots' initial contents zero.  Same errors as as_decode_attention.
+ * checksum: device uint32[256], XOR-accumulated (slot = workgroup index mod
+ * 256, folded in by a second small kernel); the XOR of the 256 slots equals
+ * the XOR of every 32-bit word of every K and V block the batch references
+ * (whole blocks), for the slots' initial contents zero.  Same errors as
+ * as_decode_attention.
  * -------------------------------------------------------------------------- */
 as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks,
                            const int32_t* block_table, const int32_t* kv_lens,

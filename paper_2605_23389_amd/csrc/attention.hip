@@ -29,6 +29,7 @@
 // cross-lane shuffles, the 4 waves through LDS.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 
@@ -181,9 +182,13 @@ __device__ __forceinline__ uint16_t f32_to_out16(float f, int out_dtype) {
   return out_dtype == AS_DTYPE_BF16 ? f32_to_bf16_rne(f) : f32_to_f16_rne(f);
 }
 
+// Results and split-KV partials leave through non-temporal stores: a workgroup
+// writes a few hundred bytes after streaming hundreds of KiB, and ordinary
+// (write-back cached) stores of that size were measured to cost far more than
+// their share of bytes next to a saturated read stream.
 __device__ __forceinline__ void store_out(char* out, size_t idx, float v, int out_dtype) {
-  if (out_dtype == AS_DTYPE_F32) reinterpret_cast<float*>(out)[idx] = v;
-  else reinterpret_cast<uint16_t*>(out)[idx] = f32_to_out16(v, out_dtype);
+  if (out_dtype == AS_DTYPE_F32) __builtin_nontemporal_store(v, reinterpret_cast<float*>(out) + idx);
+  else __builtin_nontemporal_store(f32_to_out16(v, out_dtype), reinterpret_cast<uint16_t*>(out) + idx);
 }
 
 // dot of the EPL elements a lane holds of one key row with its slice of q
@@ -278,16 +283,21 @@ struct AttnArgs {
   int32_t chunk;
   int32_t out_dtype;   // AS_DTYPE_* of out
   int32_t exact_grid;  // grid == total_items * head_groups exactly
-  int32_t direct;      // every request is one chunk: item i is request i, no item table
+  int32_t direct;      // every request is one chunk: item i is request i unless inline_plan reorders
   int32_t inline_plan; // the item table travels in the kernel arguments (InlinePlan)
   float c;             // scale * log2(e)
 };
 
 // Small launches carry their work plan in the kernel-argument segment instead
 // of having a plan kernel write it to memory first: one 32-bit word per item,
-// request index in the high and chunk index in the low 16 bits, built on the
-// host from the host copy of the lengths.  4 KiB of kernel arguments bound it.
+// built on the host from the host copy of the lengths.  4 KiB of kernel
+// arguments bound it.  A word holds (request << 20 | chunk << 10 | slot): slot
+// is the item's canonical index (request-major), which is where its partial
+// result goes, while the position of the word in the table is the order of
+// execution -- full chunks first, then the requests' last (shorter) chunks
+// from long to short, so that the launch ends on its smallest items.
 constexpr int kInlineItems = 960;
+static_assert(kInlineItems <= 1024, "chunk index and slot take 10 bits each");
 struct InlinePlan {
   uint32_t item[kInlineItems];
 };
@@ -405,14 +415,14 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
   // before the length is known (index clamped into the table row), so that the
   // length and the ids arrive together instead of one after the other.
   int4 it = make_int4(item, 0, 0, 0);
-  if (!a.direct) {
-    if (a.inline_plan) {
-      const uint32_t w = ip.item[item];
-      it.x = static_cast<int>(w >> 16);
-      it.y = static_cast<int>(w & 0xFFFFu);
-    } else {
-      it = a.items[item];
-    }
+  int slot = item;  // where this item's partial result goes
+  if (a.inline_plan) {
+    const uint32_t w = ip.item[item];
+    it.x = static_cast<int>(w >> 20);
+    it.y = static_cast<int>((w >> 10) & 0x3FFu);
+    slot = static_cast<int>(w & 0x3FFu);
+  } else if (!a.direct) {
+    it = a.items[item];
   }
   const int b = it.x;
   const int tid = threadIdx.x;
@@ -542,9 +552,12 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
       const size_t oi = (static_cast<size_t>(b) * Hq + hq) * D + d;
       store_out(a.out, oi, o, a.out_dtype);
     } else {
-      const size_t pi = static_cast<size_t>(item) * Hq + hq;
-      a.part_acc[pi * D + d] = acc;
-      if (d == 0) a.part_ml[pi] = make_float2(M * c, l);
+      const size_t pi = static_cast<size_t>(slot) * Hq + hq;
+      __builtin_nontemporal_store(acc, a.part_acc + pi * D + d);
+      if (d == 0) {
+        __builtin_nontemporal_store(M * c, &a.part_ml[pi].x);
+        __builtin_nontemporal_store(l, &a.part_ml[pi].y);
+      }
     }
   }
 }
@@ -718,14 +731,14 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   // before the length is known (index clamped into the table row), so that the
   // length and the ids arrive together instead of one after the other.
   int4 it = make_int4(item, 0, 0, 0);
-  if (!a.direct) {
-    if (a.inline_plan) {
-      const uint32_t w = ip.item[item];
-      it.x = static_cast<int>(w >> 16);
-      it.y = static_cast<int>(w & 0xFFFFu);
-    } else {
-      it = a.items[item];
-    }
+  int slot = item;  // where this item's partial result goes
+  if (a.inline_plan) {
+    const uint32_t w = ip.item[item];
+    it.x = static_cast<int>(w >> 20);
+    it.y = static_cast<int>((w >> 10) & 0x3FFu);
+    slot = static_cast<int>(w & 0x3FFu);
+  } else if (!a.direct) {
+    it = a.items[item];
   }
   const int b = it.x;
   const int tid = threadIdx.x;
@@ -852,9 +865,12 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
       const size_t oi = (static_cast<size_t>(b) * Hq + hq) * D + d;
       store_out(a.out, oi, r, a.out_dtype);
     } else {
-      const size_t pi = static_cast<size_t>(item) * Hq + hq;
-      a.part_acc[pi * D + d] = o;
-      if (d == 0) a.part_ml[pi] = make_float2(M * c, l);
+      const size_t pi = static_cast<size_t>(slot) * Hq + hq;
+      __builtin_nontemporal_store(o, a.part_acc + pi * D + d);
+      if (d == 0) {
+        __builtin_nontemporal_store(M * c, &a.part_ml[pi].x);
+        __builtin_nontemporal_store(l, &a.part_ml[pi].y);
+      }
     }
   }
 }
@@ -915,11 +931,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict_
 // XOR: the bandwidth ceiling of this access pattern.
 template <int NLD>
 __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab_bytes,
-                                                         uint32_t* __restrict__ checksum) {
+                                                         uint32_t* __restrict__ wg_sums) {
   const int Hkv = a.num_kv_heads;
   const int item = blockIdx.x / Hkv;
   const int h = blockIdx.x - item * Hkv;
-  if (!a.exact_grid && item >= a.hdr->total_items) return;
+  if (!a.exact_grid && item >= a.hdr->total_items) {
+    if (threadIdx.x == 0) wg_sums[blockIdx.x] = 0;
+    return;
+  }
   int4 it;
   if (a.direct) it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
   else it = a.items[item];
@@ -929,8 +948,7 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int t0 = it.y * a.chunk;
-  const int ntok = min(kv_len - t0, a.chunk);
-  if (ntok <= 0) return;
+  const int ntok = max(min(kv_len - t0, a.chunk), 0);
   const int ntiles = (ntok + kBlock - 1) / kBlock;
   const int my_tiles = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
   int my_id = 0;
@@ -966,7 +984,9 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab
   }
   uint32_t r = x.x ^ x.y ^ x.z ^ x.w;
   for (int off = 32; off > 0; off >>= 1) r ^= __shfl_xor(r, off);
-  // one atomic per workgroup
+  // one word per workgroup, folded into the caller's 256 slots by a second
+  // small kernel (an atomic per workgroup next to the saturated read stream
+  // costs several per cent of the bandwidth this kernel exists to measure)
   __shared__ uint32_t wave_sum[kWaves];
   if (lane == 0) wave_sum[wave] = r;
   __syncthreads();
@@ -974,8 +994,16 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab
     uint32_t t = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) t ^= wave_sum[w];
-    atomicXor(checksum + (blockIdx.x & 255), t);
+    __builtin_nontemporal_store(t, wg_sums + blockIdx.x);
   }
+}
+
+// checksum[s] ^= XOR of wg_sums[i] over i = s (mod 256)
+__global__ __launch_bounds__(256) void sweep_fold_kernel(const uint32_t* __restrict__ wg_sums, int64_t n,
+                                                         uint32_t* __restrict__ checksum) {
+  uint32_t t = 0;
+  for (int64_t i = threadIdx.x; i < n; i += 256) t ^= wg_sums[i];
+  checksum[threadIdx.x] ^= t;
 }
 
 // ------------------------------------------------------------------ host side
@@ -995,7 +1023,7 @@ int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
   // per item: its per-item overhead is about 4x, so its best chunk about 2x
   const int group = p.num_q_heads / p.num_kv_heads;
   const bool wide = p.dtype != AS_DTYPE_F32 && p.head_dim == 128 && group >= 4;
-  int chunk = static_cast<int>(std::sqrt(wide ? t : t / 4.0));
+  int chunk = static_cast<int>(std::sqrt(wide ? 6.0 * t : 1.5 * t));
   chunk = (chunk + 63) / 64 * 64;
   if (chunk < 256) chunk = 256;
   if (chunk > kMaxChunk) chunk = kMaxChunk;
@@ -1078,20 +1106,29 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
   }
   out->w = layout_for(*p, out->items);
   // small launches with known lengths: build the plan here and ship it in the
-  // kernel arguments
+  // kernel arguments (also when no request is split: the table then only puts
+  // the requests in longest-first order)
   out->use_inline = false;
-  if (kv_lens_host && out->any_split && out->items <= kInlineItems && p->batch < 2 * kInlineItems) {
-    bool fits = true;
-    int64_t n = 0;
-    for (int b = 0; b < p->batch && fits; ++b) {
+  if (kv_lens_host && out->items <= kInlineItems) {
+    // canonical slots, request-major; full chunks go to the front of the
+    // execution order as they are met
+    uint32_t n = 0, pos = 0;
+    struct Last { int32_t tokens; uint32_t word; };
+    Last last[kInlineItems];
+    int nlast = 0;
+    for (int b = 0; b < p->batch; ++b) {
       const int nch = (kv_lens_host[b] + out->chunk - 1) / out->chunk;
-      fits = nch <= 0xFFFF;
       out->icu.first[b] = static_cast<uint16_t>(n);
-      for (int c = 0; c < nch && fits; ++c)
-        out->ip.item[n++] = (static_cast<uint32_t>(b) << 16) | static_cast<uint32_t>(c);
+      for (int c = 0; c < nch; ++c, ++n) {
+        const uint32_t word = (static_cast<uint32_t>(b) << 20) | (static_cast<uint32_t>(c) << 10) | n;
+        if (c + 1 < nch) out->ip.item[pos++] = word;
+        else last[nlast++] = Last{kv_lens_host[b] - c * out->chunk, word};
+      }
     }
     out->icu.first[p->batch] = static_cast<uint16_t>(n);
-    out->use_inline = fits && p->batch <= 0xFFFF;
+    std::stable_sort(last, last + nlast, [](const Last& x, const Last& y) { return x.tokens > y.tokens; });
+    for (int i = 0; i < nlast; ++i) out->ip.item[pos++] = last[i].word;
+    out->use_inline = true;
   }
   if (out->items * p->num_q_heads > 0x7FFFFFFFLL)
     return als::fail(AS_ERANGE, "%s: %lld work items exceed the launch limit", what,
@@ -1265,12 +1302,18 @@ extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks
   a.inline_plan = 0;
   const size_t esz = p->dtype == AS_DTYPE_F32 ? 4 : 2;
   const size_t slab = static_cast<size_t>(kBlock) * p->head_dim * esz;
-  const dim3 grid(static_cast<unsigned>(ck.items * p->num_kv_heads));
+  const int64_t nwg = ck.items * p->num_kv_heads;
+  const dim3 grid(static_cast<unsigned>(nwg));
+  // per-workgroup words go where the attention call keeps its partial sums:
+  // items * H_q * D floats, never fewer than items * H_kv words
+  uint32_t* wg_sums = reinterpret_cast<uint32_t*>(a.part_acc);
   switch (slab / 1024) {
-    case 2: hipLaunchKernelGGL(sweep_kernel<2>, grid, dim3(kThreads), 0, s, a, slab, checksum); break;
-    case 4: hipLaunchKernelGGL(sweep_kernel<4>, grid, dim3(kThreads), 0, s, a, slab, checksum); break;
-    default: hipLaunchKernelGGL(sweep_kernel<8>, grid, dim3(kThreads), 0, s, a, slab, checksum); break;
+    case 2: hipLaunchKernelGGL(sweep_kernel<2>, grid, dim3(kThreads), 0, s, a, slab, wg_sums); break;
+    case 4: hipLaunchKernelGGL(sweep_kernel<4>, grid, dim3(kThreads), 0, s, a, slab, wg_sums); break;
+    default: hipLaunchKernelGGL(sweep_kernel<8>, grid, dim3(kThreads), 0, s, a, slab, wg_sums); break;
   }
+  ALS_HIP_CHECK(hipGetLastError());
+  hipLaunchKernelGGL(sweep_fold_kernel, dim3(1), dim3(256), 0, s, wg_sums, nwg, checksum);
   ALS_HIP_CHECK(hipGetLastError());
   return AS_OK;
 }
