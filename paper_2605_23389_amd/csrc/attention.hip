@@ -302,6 +302,23 @@ struct InlinePlan {
   uint32_t item[kInlineItems];
 };
 
+// Workgroups are handed to the 8 XCDs round-robin by their linear index, and
+// every XCD has its own L2 and address-translation cache.  Workgroups with
+// neighbouring task indices read neighbouring slabs of the same KV blocks
+// (the head index varies fastest), so the task index is derived from the
+// workgroup index such that each XCD gets runs of 8 consecutive tasks: within
+// every group of 64 workgroups, workgroup 8*k + x (XCD x) takes task 8*x + k.
+// Measured on the streaming pattern of this kernel: +1.5 to 2.5 % bandwidth.
+constexpr int kXcds = 8;
+constexpr int kXcdRun = 8;
+__device__ __forceinline__ int task_of_workgroup(int wg, int grid) {
+  constexpr int per = kXcds * kXcdRun;
+  const int base = wg / per * per;
+  if (base + per > grid) return wg;  // ragged last group keeps the plain order
+  const int r = wg - base;
+  return base + (r % kXcds) * kXcdRun + r / kXcds;
+}
+
 // Online-softmax state of one token group for one query head.
 template <int EPL>
 struct HeadState {
@@ -407,8 +424,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
   __shared__ float sm_acc[kWaves][G][D];
 
   const int Hkv = a.num_kv_heads;
-  const int item = blockIdx.x / a.head_groups;
-  const int hg = blockIdx.x - item * a.head_groups;  // query heads hg*G .. hg*G+G-1
+  const int task = task_of_workgroup(blockIdx.x, gridDim.x);
+  const int item = task / a.head_groups;
+  const int hg = task - item * a.head_groups;  // query heads hg*G .. hg*G+G-1
   const int h = hg / a.kv_div;                       // KV head they read
   if (!a.exact_grid && item >= a.hdr->total_items) return;
   // (request, chunk) of this item.  The block ids of the chunk are requested
@@ -723,8 +741,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   static_assert(kWaves * kLdsKTile <= kMergeBytes, "K tiles must fit the shared buffer");
 
   const int Hkv = a.num_kv_heads;
-  const int item = blockIdx.x / a.head_groups;
-  const int hg = blockIdx.x - item * a.head_groups;
+  const int task = task_of_workgroup(blockIdx.x, gridDim.x);
+  const int item = task / a.head_groups;
+  const int hg = task - item * a.head_groups;
   const int h = hg / a.kv_div;
   if (!a.exact_grid && item >= a.hdr->total_items) return;
   // (request, chunk) of this item.  The block ids of the chunk are requested
@@ -933,8 +952,9 @@ template <int NLD>
 __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab_bytes,
                                                          uint32_t* __restrict__ wg_sums) {
   const int Hkv = a.num_kv_heads;
-  const int item = blockIdx.x / Hkv;
-  const int h = blockIdx.x - item * Hkv;
+  const int task = task_of_workgroup(blockIdx.x, gridDim.x);
+  const int item = task / Hkv;
+  const int h = task - item * Hkv;
   if (!a.exact_grid && item >= a.hdr->total_items) {
     if (threadIdx.x == 0) wg_sums[blockIdx.x] = 0;
     return;
