@@ -949,7 +949,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict_
 // Streams the same K/V bytes with the same work split and folds them with
 // XOR: the bandwidth ceiling of this access pattern.
 template <int NLD>
-__global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab_bytes,
+__global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, InlinePlan ip, size_t slab_bytes,
                                                          uint32_t* __restrict__ wg_sums) {
   const int Hkv = a.num_kv_heads;
   const int task = task_of_workgroup(blockIdx.x, gridDim.x);
@@ -959,11 +959,18 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(AttnArgs a, size_t slab
     if (threadIdx.x == 0) wg_sums[blockIdx.x] = 0;
     return;
   }
-  int4 it;
-  if (a.direct) it = make_int4(item, 0, min(a.kv_lens[item], a.max_blocks_per_seq * kBlock), 0);
-  else it = a.items[item];
+  // the same three sources of the work plan as the attention kernels
+  int4 it = make_int4(item, 0, 0, 0);
+  if (a.inline_plan) {
+    const uint32_t w = ip.item[item];
+    it.x = static_cast<int>(w >> 20);
+    it.y = static_cast<int>((w >> 10) & 0x3FFu);
+  } else if (!a.direct) {
+    it = a.items[item];
+  }
   const int b = it.x;
-  const int kv_len = it.z;  // already cut to the block_table row
+  const int kv_len = (a.direct || a.inline_plan) ? min(a.kv_lens[b], a.max_blocks_per_seq * kBlock)
+                                                 : it.z;  // cut to the block_table row
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1313,13 +1320,11 @@ extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks
   if (st != AS_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  // the sweep always reads its plan from the workspace (never from kernel arguments)
-  if (!(ck.exact && !ck.any_split)) {
+  if (!(ck.exact && !ck.any_split) && !ck.use_inline) {
     st = run_plan(*p, ck, kv_lens, ws, s);
     if (st != AS_OK) return st;
   }
   AttnArgs a = make_args(*p, ck, k_blocks, k_blocks, v_blocks, block_table, kv_lens, checksum, ws);
-  a.inline_plan = 0;
   const size_t esz = p->dtype == AS_DTYPE_F32 ? 4 : 2;
   const size_t slab = static_cast<size_t>(kBlock) * p->head_dim * esz;
   const int64_t nwg = ck.items * p->num_kv_heads;
@@ -1328,9 +1333,9 @@ extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks
   // items * H_q * D floats, never fewer than items * H_kv words
   uint32_t* wg_sums = reinterpret_cast<uint32_t*>(a.part_acc);
   switch (slab / 1024) {
-    case 2: hipLaunchKernelGGL(sweep_kernel<2>, grid, dim3(kThreads), 0, s, a, slab, wg_sums); break;
-    case 4: hipLaunchKernelGGL(sweep_kernel<4>, grid, dim3(kThreads), 0, s, a, slab, wg_sums); break;
-    default: hipLaunchKernelGGL(sweep_kernel<8>, grid, dim3(kThreads), 0, s, a, slab, wg_sums); break;
+    case 2: hipLaunchKernelGGL(sweep_kernel<2>, grid, dim3(kThreads), 0, s, a, ck.ip, slab, wg_sums); break;
+    case 4: hipLaunchKernelGGL(sweep_kernel<4>, grid, dim3(kThreads), 0, s, a, ck.ip, slab, wg_sums); break;
+    default: hipLaunchKernelGGL(sweep_kernel<8>, grid, dim3(kThreads), 0, s, a, ck.ip, slab, wg_sums); break;
   }
   ALS_HIP_CHECK(hipGetLastError());
   hipLaunchKernelGGL(sweep_fold_kernel, dim3(1), dim3(256), 0, s, wg_sums, nwg, checksum);
