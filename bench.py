@@ -108,10 +108,16 @@ def pipeline_leg(args, torch, als, harness, traffic, wl, log):
     pipe = als.Pipeline(2)
     compute = torch.cuda.current_stream()
 
+    # the same batches out of a paged host pool: every block at a random arena slot
+    rs = np.random.default_rng(args.seed + 40)
+    for jb in jobs:
+        jb["src_paged"] = rs.integers(0, arena_blocks, jb["nblocks"]).astype(np.int64)
+    src_key = ["src"]
+
     def stage(jb):
         pipe.begin_stage(jb["buf"])
         for l in range(layers):
-            als.stage_kv(host_k[l], host_v[l], jb["src"], dev_k[l], dev_v[l], jb["dst"], block_bytes,
+            als.stage_kv(host_k[l], host_v[l], jb[src_key[0]], dev_k[l], dev_v[l], jb["dst"], block_bytes,
                          stream=pipe.stream)
         pipe.end_stage(jb["buf"])
 
@@ -150,8 +156,23 @@ def pipeline_leg(args, torch, als, harness, traffic, wl, log):
     t_copy = min(wall(copies_only) for _ in range(2))
     t_attn = min(wall(attn_only) for _ in range(3))
     t_pipe = min(wall(pipelined) for _ in range(2))
-    pipe.destroy()
     moved = sum(jb["nblocks"] for jb in jobs) * block_bytes * 2 * layers
+    # paged host pool: automatic choice (the gather kernel), alone and pipelined; per-block DMA
+    # copies on the first batch only (they are an order of magnitude slower)
+    src_key[0] = "src_paged"
+    copies_only()
+    t_copy_paged = min(wall(copies_only) for _ in range(2))
+    t_pipe_paged = min(wall(pipelined) for _ in range(2))
+    als.stage_set_policy(als.STAGE_DMA)
+    try:
+        t_dma_first = wall(lambda: stage(jobs[0]))
+    finally:
+        als.stage_set_policy(als.STAGE_AUTO)
+    dma_first_bytes = jobs[0]["nblocks"] * block_bytes * 2 * layers
+    src_key[0] = "src"
+    pipe.destroy()
+    log(f"pipeline, paged host pool: copy {moved / t_copy_paged / 1e9:.1f} GB/s (gather kernel), pipelined "
+        f"{t_pipe_paged * 1e3:.1f} ms; per-block DMA copies {dma_first_bytes / t_dma_first / 1e9:.1f} GB/s")
     attn_bytes = sum(traffic.attention_bytes(jb["lens"], Hq, Hkv, D, 2, 2) for jb in jobs) * layers
     log(f"pipeline: copy {t_copy * 1e3:.1f} ms ({moved / t_copy / 1e9:.1f} GB/s), attn {t_attn * 1e3:.2f} ms, "
         f"pipelined {t_pipe * 1e3:.1f} ms")
@@ -165,6 +186,14 @@ def pipeline_leg(args, torch, als, harness, traffic, wl, log):
         "overlap_vs_serial": round((t_copy + t_attn) / t_pipe, 3),
         "pipelined_over_max": round(t_pipe / max(t_copy, t_attn), 3),
         "note": "copy-bound regime: staging over PCIe dominates; attention of the previous batch hides under it",
+        "paged_host_pool": {
+            "h2d_GBs_gather_kernel": round(moved / t_copy_paged / 1e9, 1),
+            "pipelined_ms": round(t_pipe_paged * 1e3, 2),
+            "pipelined_over_max": round(t_pipe_paged / max(t_copy_paged, t_attn), 3),
+            "h2d_GBs_dma_copy_per_block": round(dma_first_bytes / t_dma_first / 1e9, 1),
+            "note": "every 32 KiB block at a random slot of the pinned arena (runs of one block); the library "
+                    "then moves blocks with its copy kernel (64 workgroups reading host memory over the link); "
+                    "one DMA copy per block, timed on the first batch only, for comparison"},
     }
 
 

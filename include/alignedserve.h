@@ -271,8 +271,12 @@ as_status as_sched_running(const as_sched* s, int32_t* ids, int32_t* kv_lens, in
  *   host_k + src_ids[i] * block_bytes  ->  dev_k + dst_ids[i] * block_bytes
  * and the same for host_v -> dev_v (host_v/dev_v may both be null to move one
  * pool only).  Runs in which src and dst ids both advance by one are merged
- * into a single copy.  host_* must be pinned (hipHostMalloc) memory; the id
- * arrays are host arrays and are consumed before the call returns.
+ * into a single DMA copy; when the runs are short (a paged host pool hands out
+ * scattered blocks) the blocks are instead moved by a small copy kernel that
+ * reads the pinned host memory over the link (see as_stage_set_policy).  The
+ * result is the same either way.  host_* must be pinned (hipHostMalloc)
+ * memory; the id arrays are host arrays and are consumed before the call
+ * returns.  Blocks within one call must not overlap each other.
  * num_src_blocks / num_dst_blocks bound the ids.  The caller orders the
  * copies against consumers with events (see as_pipeline_* below).
  * Errors: AS_EINVAL (null, m < 0, block_bytes == 0 or not a multiple of 16,
@@ -282,6 +286,16 @@ as_status as_stage_kv(const void* host_k, const void* host_v, const int64_t* src
                       int64_t num_src_blocks, void* dev_k, void* dev_v,
                       const int32_t* dst_ids, int32_t num_dst_blocks, int32_t m,
                       size_t block_bytes, void* hip_stream);
+
+/* How as_stage_kv / as_unstage_kv move blocks (process-wide, default AUTO):
+ *   AS_STAGE_AUTO    DMA copies when a run averages >= 8 MiB, else the kernel
+ *   AS_STAGE_DMA     always one hipMemcpyAsync per run (SDMA engines)
+ *   AS_STAGE_KERNEL  always the copy kernel (64 workgroups on the given stream)
+ * Errors: AS_EINVAL for any other value. */
+#define AS_STAGE_AUTO 0
+#define AS_STAGE_DMA 1
+#define AS_STAGE_KERNEL 2
+as_status as_stage_set_policy(int32_t policy);
 
 /* The reverse direction (eviction of a request's blocks to the host pool,
  * Section 3.4 case 3): dev + src_ids[i] -> host + dst_ids[i]. */

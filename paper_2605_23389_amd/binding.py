@@ -21,6 +21,7 @@ STATUS_NAMES = {0: "AS_OK", 1: "AS_EINVAL", 2: "AS_ERANGE", 3: "AS_EWORKSPACE",
                 4: "AS_EUNSUPPORTED", 5: "AS_EHIP"}
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 ATTN_REUSE_PLAN, ATTN_NO_MFMA = 1, 2
+STAGE_AUTO, STAGE_DMA, STAGE_KERNEL = 0, 1, 2
 
 EXPORTS = [
     "as_version", "as_last_error", "as_aligned_batch", "as_decode_attention_workspace",
@@ -30,7 +31,7 @@ EXPORTS = [
     "as_qtree_create", "as_qtree_destroy", "as_qtree_insert", "as_qtree_remove", "as_qtree_size",
     "as_qtree_next_batch", "as_dfs_batches", "as_kv_append", "as_sched_create", "as_sched_destroy",
     "as_sched_push_candidate_batch", "as_sched_push_candidate_request", "as_sched_step",
-    "as_sched_state", "as_sched_running",
+    "as_sched_state", "as_sched_running", "as_stage_set_policy",
 ]
 
 
@@ -85,6 +86,8 @@ def load() -> C.CDLL:
     lib.as_unstage_kv.restype = C.c_int
     lib.as_unstage_kv.argtypes = [vp, vp, i64p, C.c_int64, vp, vp, i32p, C.c_int32, C.c_int32,
                                   C.c_size_t, vp]
+    lib.as_stage_set_policy.restype = C.c_int
+    lib.as_stage_set_policy.argtypes = [C.c_int32]
     lib.as_pipeline_create.restype = C.c_int
     lib.as_pipeline_create.argtypes = [C.POINTER(vp), C.c_int32]
     lib.as_pipeline_stream.restype = vp
@@ -268,6 +271,11 @@ def _move(fn, host_k, host_v, host_ids, dev_k, dev_v, dev_ids, block_bytes, stre
               _ptr(hid, C.c_int64), n_host, dev_k.data_ptr(),
               None if dev_v is None else dev_v.data_ptr(), _ptr(did, C.c_int32), n_dev,
               int(hid.shape[0]), int(block_bytes), _stream_ptr(stream)))
+
+
+def stage_set_policy(policy: int):
+    """How stage_kv / unstage_kv move blocks: STAGE_AUTO, STAGE_DMA or STAGE_KERNEL."""
+    _check(load().as_stage_set_policy(int(policy)))
 
 
 def stage_kv(host_k, host_v, src_ids, dev_k, dev_v, dst_ids, block_bytes: int, stream=None):

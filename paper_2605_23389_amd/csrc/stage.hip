@@ -6,15 +6,81 @@
 // PCIe when no peer GPU buffers it), and the next batch is prefetched
 // asynchronously (Fig. 4 step 4) so the transfer overlaps decoding of the
 // running batch (Section 4.4).  Section 3.4 case 3 is the reverse move
-// (eviction).  The copies go through the SDMA engines (hipMemcpyAsync on
-// pinned memory), which leaves every compute unit to the attention kernel.
+// (eviction).
+//
+// Two ways of moving the blocks, chosen per call (as_stage_set_policy):
+//  * DMA copies: one hipMemcpyAsync per run of blocks whose host and device
+//    ids both advance by one.  The SDMA engines move the data and every
+//    compute unit stays with the attention kernel.  Best when runs are long.
+//  * Gather kernel: a paged host pool hands out scattered blocks, and one DMA
+//    copy per 32-128 KiB block is bound by the per-copy cost, not by the
+//    link.  A small persistent grid (64 workgroups) then reads the pinned host
+//    blocks directly over the link with 128-bit loads and writes them to their
+//    HBM slots (or the reverse); the block ids travel in the kernel arguments,
+//    256 per launch, so nothing is allocated and nothing outlives the call.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 
 #include "common.h"
 
 namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+std::atomic<int32_t> g_policy{AS_STAGE_AUTO};
+
+// Below this many bytes per run, on average, the gather kernel is used under
+// AS_STAGE_AUTO.  Measured on MI355X / PCIe Gen5 (2 GiB per pool, host to
+// device): DMA copies reach 2.9 GB/s with 32 KiB runs, 10.7 with 128 KiB, 27.7
+// with 512 KiB, 45 with 2 MiB, 53.5 with 8 MiB and 57.6 GB/s as one copy; the
+// kernel 55-57 GB/s for every run length.
+constexpr size_t kAutoRunBytes = 8u << 20;
+
+constexpr int kGatherIds = 256;        // (host id, device id) pairs per launch
+constexpr int kGatherGrid = 64;        // persistent workgroups
+constexpr int kPartBytes = 16 * 1024;  // one task: 256 threads x 4 x 16 B
+struct GatherIds {
+  int64_t host[kGatherIds];
+  int32_t dev[kGatherIds];
+};
+
+// task = (block i, part, pool): copies up to 16 KiB of one block of one pool.
+// All four loads of a thread are issued before its stores, so a workgroup keeps
+// 16 KiB in flight over the link.
+__global__ __launch_bounds__(256) void gather_kernel(char* host_k, char* host_v, char* dev_k, char* dev_v,
+                                                     GatherIds ids, int n, size_t block_bytes,
+                                                     int to_device) {
+  const int parts = static_cast<int>((block_bytes + kPartBytes - 1) / kPartBytes);
+  const int pools = host_v ? 2 : 1;
+  const int tasks = n * parts * pools;
+  for (int task = blockIdx.x; task < tasks; task += gridDim.x) {
+    const int pool = task % pools;
+    const int rest = task / pools;
+    const int part = rest % parts;
+    const int i = rest / parts;
+    const size_t in_block = static_cast<size_t>(part) * kPartBytes;
+    const size_t hoff = static_cast<size_t>(ids.host[i]) * block_bytes + in_block;
+    const size_t doff = static_cast<size_t>(ids.dev[i]) * block_bytes + in_block;
+    char* h = (pool ? host_v : host_k) + hoff;
+    char* d = (pool ? dev_v : dev_k) + doff;
+    const char* src = to_device ? h : d;
+    char* dst = to_device ? d : h;
+    const size_t bytes = block_bytes - in_block < kPartBytes ? block_bytes - in_block : kPartBytes;
+    u32x4 r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const size_t off = static_cast<size_t>(k) * 4096 + threadIdx.x * 16;
+      if (off < bytes) r[k] = *reinterpret_cast<const u32x4*>(src + off);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const size_t off = static_cast<size_t>(k) * 4096 + threadIdx.x * 16;
+      if (off < bytes) *reinterpret_cast<u32x4*>(dst + off) = r[k];
+    }
+  }
+}
 
 bool is_pinned_host(const void* p) {
   hipPointerAttribute_t attr;
@@ -55,6 +121,42 @@ as_status move_blocks(const char* what, char* host_k, char* host_v, const int64_
     return als::fail(AS_EINVAL, "%s: host pool is not pinned (hipHostMalloc) memory", what);
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int64_t runs = 1;
+  for (int32_t i = 1; i < m; ++i)
+    runs += !(h_ids[i] == h_ids[i - 1] + 1 && d_ids[i] == d_ids[i - 1] + 1);
+  const int32_t policy = g_policy.load(std::memory_order_relaxed);
+  bool use_kernel = policy == AS_STAGE_KERNEL ||
+                    (policy == AS_STAGE_AUTO &&
+                     static_cast<size_t>(m) * block_bytes < static_cast<size_t>(runs) * kAutoRunBytes);
+  char *hk_dev = nullptr, *hv_dev = nullptr;
+  if (use_kernel) {
+    // the address the device uses for the pinned host pool; memory that is
+    // pinned but not mapped into the device's address space keeps the DMA path
+    if (hipHostGetDevicePointer(reinterpret_cast<void**>(&hk_dev), host_k, 0) != hipSuccess ||
+        (host_v && hipHostGetDevicePointer(reinterpret_cast<void**>(&hv_dev), host_v, 0) != hipSuccess)) {
+      (void)hipGetLastError();
+      if (policy == AS_STAGE_KERNEL)
+        return als::fail(AS_EINVAL, "%s: host pool is not mapped into the device address space", what);
+      use_kernel = false;
+    }
+  }
+  if (use_kernel) {
+    const int parts = static_cast<int>((block_bytes + kPartBytes - 1) / kPartBytes);
+    for (int32_t i = 0; i < m; i += kGatherIds) {
+      GatherIds ids;
+      const int n = m - i < kGatherIds ? m - i : kGatherIds;
+      for (int j = 0; j < n; ++j) {
+        ids.host[j] = h_ids[i + j];
+        ids.dev[j] = d_ids[i + j];
+      }
+      const int64_t tasks = static_cast<int64_t>(n) * parts * (host_v ? 2 : 1);
+      const dim3 grid(static_cast<unsigned>(tasks < kGatherGrid ? tasks : kGatherGrid));
+      hipLaunchKernelGGL(gather_kernel, grid, dim3(256), 0, stream, hk_dev, hv_dev, dev_k, dev_v, ids, n,
+                         block_bytes, to_device ? 1 : 0);
+      ALS_HIP_CHECK(hipGetLastError());
+    }
+    return AS_OK;
+  }
   int32_t i = 0;
   while (i < m) {
     int32_t j = i + 1;
@@ -77,6 +179,13 @@ as_status move_blocks(const char* what, char* host_k, char* host_v, const int64_
 }
 
 }  // namespace
+
+extern "C" as_status as_stage_set_policy(int32_t policy) {
+  if (policy != AS_STAGE_AUTO && policy != AS_STAGE_DMA && policy != AS_STAGE_KERNEL)
+    return als::fail(AS_EINVAL, "as_stage_set_policy: unknown policy %d", policy);
+  g_policy.store(policy, std::memory_order_relaxed);
+  return AS_OK;
+}
 
 extern "C" as_status as_stage_kv(const void* host_k, const void* host_v, const int64_t* src_ids,
                                  int64_t num_src_blocks, void* dev_k, void* dev_v,

@@ -161,3 +161,53 @@ def test_double_buffered_pipeline_orders_copies_and_attention(lib):
         got = out.double().cpu().numpy()
         assert np.isfinite(got).all()
         assert np.abs(got - ref).max() <= 1.5e-2
+
+
+@pytest.mark.parametrize("policy", ["auto", "dma", "kernel"])
+@pytest.mark.parametrize("block_bytes", [32768, 16384 + 4096 + 48, 4096, 131072])
+def test_stage_paths_agree_byte_for_byte(lib, policy, block_bytes):
+    """Every way of moving the blocks (DMA copies per run, the gather kernel,
+    or the automatic choice) leaves the same bytes in the same slots, in both
+    directions, for block sizes with and without a ragged last part, and for
+    more blocks than one kernel launch carries ids for."""
+    import torch
+    from paper_2605_23389_amd import binding as als
+    rng = np.random.default_rng(block_bytes)
+    n_host, n_dev, m = 700, 640, 600
+    hk, hv = _pinned((n_host, block_bytes), torch.uint8), _pinned((n_host, block_bytes), torch.uint8)
+    hk.copy_(torch.from_numpy(rng.integers(0, 256, (n_host, block_bytes), dtype=np.uint8)))
+    hv.copy_(torch.from_numpy(rng.integers(0, 256, (n_host, block_bytes), dtype=np.uint8)))
+    dk = torch.full((n_dev, block_bytes), 0xAB, dtype=torch.uint8, device="cuda")
+    dv = torch.full((n_dev, block_bytes), 0xCD, dtype=torch.uint8, device="cuda")
+    src = rng.permutation(n_host)[:m].astype(np.int64)      # scattered: runs of one block
+    dst = rng.permutation(n_dev)[:m].astype(np.int32)
+    src[100:140] = np.arange(300, 340)                      # plus one long run (may repeat earlier ids: reads only)
+    dst_run = np.setdiff1d(np.arange(n_dev), np.delete(dst, np.s_[100:140]))[:40]
+    assert len(dst_run) == 40 and np.all(np.diff(dst_run) >= 1)
+    dst[100:140] = dst_run
+    assert len(set(dst.tolist())) == m
+    s = torch.cuda.Stream()
+    als.stage_set_policy({"auto": als.STAGE_AUTO, "dma": als.STAGE_DMA, "kernel": als.STAGE_KERNEL}[policy])
+    try:
+        lib.stage_kv(hk, hv, src, dk, dv, dst, block_bytes, stream=s)
+        s.synchronize()
+        dk_h, dv_h = dk.cpu().numpy(), dv.cpu().numpy()
+        assert np.array_equal(dk_h[dst], hk.numpy()[src]) and np.array_equal(dv_h[dst], hv.numpy()[src])
+        untouched = np.setdiff1d(np.arange(n_dev), dst)
+        assert (dk_h[untouched] == 0xAB).all() and (dv_h[untouched] == 0xCD).all()
+        # eviction: device -> distinct host slots
+        hk2 = _pinned((n_host, block_bytes), torch.uint8); hk2.zero_()
+        hdst = rng.permutation(n_host)[:m].astype(np.int64)
+        lib.unstage_kv(hk2, None, hdst, dk, None, dst, block_bytes, stream=s)
+        s.synchronize()
+        assert np.array_equal(hk2.numpy()[hdst], dk_h[dst])
+        rest = np.setdiff1d(np.arange(n_host), hdst)
+        assert (hk2.numpy()[rest] == 0).all()
+    finally:
+        als.stage_set_policy(als.STAGE_AUTO)
+
+
+def test_stage_policy_rejects_unknown_value(lib):
+    from paper_2605_23389_amd import binding as als
+    with pytest.raises(als.AlignedServeError):
+        als.stage_set_policy(7)
