@@ -566,6 +566,43 @@ def main():
         log(f"cfg1 x32 layers: eager {t_eager * 1e6:.0f} us, graph {t_graph * 1e6:.0f} us")
         del pools, graph
 
+        # ---------------- context: the dense part of one decode layer for the same 64 requests, with
+        # LIBRARY GEMMs (torch.matmul -> hipBLASLt / rocBLAS), random weights, Llama-7B shapes
+        # (h 4096, MLP 11008).  Not part of this library and not in any headline number: it places the
+        # attention time next to the per-layer cost of the operators of the paper's Table 1.
+        hdim, mlp = Hq * D, 11008
+        gw = torch.Generator(device="cuda").manual_seed(args.seed + 77)
+        wsets = []
+        for _ in range(3):      # 3 x 0.4 GB of weights in rotation: more than the 256 MB Infinity Cache
+            mk = lambda r, c: (torch.randn((r, c), generator=gw, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            wsets.append(dict(qkv=mk(hdim, 3 * hdim), o=mk(hdim, hdim), gu=mk(hdim, 2 * mlp), down=mk(mlp, hdim)))
+        xin = torch.randn((len(lens1), hdim), generator=gw, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        turn = [0]
+
+        def dense_part():
+            w = wsets[turn[0] % 3]
+            turn[0] += 1
+            qkv = xin @ w["qkv"]
+            o = qkv[:, :hdim] @ w["o"]
+            gu = o @ w["gu"]
+            act = torch.nn.functional.silu(gu[:, :mlp]) * gu[:, mlp:]
+            return act @ w["down"]
+        for _ in range(3):
+            dense_part()
+        t_dense = time_region(dense_part, 30, torch) / 30
+        wbytes = 2 * (hdim * 3 * hdim + hdim * hdim + hdim * 2 * mlp + mlp * hdim)
+        result["decode_layer_context"] = {
+            "dense_us": round(t_dense * 1e6, 1), "attention_us": round(s1 * 1e6, 1),
+            "attention_share_pct": round(100 * s1 / (s1 + t_dense), 1),
+            "weight_bytes": wbytes, "dense_GBs": round(wbytes / t_dense / 1e9, 0),
+            "note": "configs[1] batch (64 requests, mean KV 1404): QKV, output and MLP projections of one "
+                    "Llama-7B-shaped layer through library GEMMs (torch.matmul; norms, RoPE and residuals "
+                    "left out) next to this library's attention for the same layer; context for the paper's "
+                    "Table 1 (attention moves 2*s*h KV elements per token, the projections 12*h^2 weights per "
+                    "batch), not a product path"}
+        log(f"decode layer context: dense {t_dense * 1e6:.1f} us vs attention {s1 * 1e6:.1f} us")
+        del wsets
+
     if not args.skip_extra:
         # free the big pool before the other configurations
         del batches_r

@@ -66,7 +66,7 @@ template <> struct Elem<f16_t> { static constexpr int kPerLoad = 8; };
 // ------------------------------------------------------------------ workspace
 // [0,256)            PlanHeader
 // cu_chunks          int32[batch + 1]   first item of each request
-// items              int4[max_items]    (request, chunk index, kv_len, 0)
+// items              int4[max_items]    (request, chunk index, kv_len, slot of the partial result)
 // part_ml            float2[max_items * H_q]   (running max in log2 units, sum)
 // part_acc           float[max_items * H_q * D]
 struct PlanHeader {
@@ -94,52 +94,88 @@ WorkspaceLayout layout_for(const as_attn_params& p, int64_t max_items) {
 }
 
 // ------------------------------------------------------------------ plan
-// One workgroup.  cu_chunks = exclusive scan of per-request chunk counts
-// (a request with kv_len <= 0 still gets one item, which writes zeros), then
-// item i -> (request, chunk) by binary search in cu_chunks.
+// Builds the item table on the device (launches too large for the plan that
+// travels in the kernel arguments, and calls without host lengths).  A request
+// of L tokens has n = ceil(L / chunk) chunks (one when L <= 0: it writes
+// zeros).  Order of execution: every full chunk first (request-major), then
+// each request's last chunk in request order, so that a launch ends on short
+// items.  An item's partial result goes to its canonical slot
+// cu_chunks[request] + chunk, cu_chunks = exclusive scan of n.
+// Every workgroup repeats the two 256-entry scans in LDS (thread t covers
+// `per` consecutive requests) and fills its share of the table; the requests
+// inside a thread's segment are walked linearly.  Workgroup 0 also writes
+// cu_chunks and the header.
 __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ kv_lens, int batch,
                                                    int chunk, int max_len, PlanHeader* __restrict__ hdr,
                                                    int32_t* __restrict__ cu_chunks,
                                                    int4* __restrict__ items, int64_t max_items) {
-  __shared__ int32_t part[256];
+  __shared__ int32_t all_incl[256];   // inclusive scan of chunks per thread segment
+  __shared__ int32_t full_incl[256];  // inclusive scan of (chunks - 1)
   const int tid = threadIdx.x;
   const int per = (batch + 255) / 256;
-  const int lo = tid * per;
+  const int lo = min(batch, tid * per);
   const int hi = min(batch, lo + per);
+  auto chunks_of = [&](int b) {
+    const int32_t L = min(kv_lens[b], max_len);
+    return L > 0 ? (L + chunk - 1) / chunk : 1;
+  };
   int32_t sum = 0;
-  for (int b = lo; b < hi; ++b) {
-    const int32_t L = min(kv_lens[b], max_len);
-    sum += L > 0 ? (L + chunk - 1) / chunk : 1;
-  }
-  part[tid] = sum;
+  for (int b = lo; b < hi; ++b) sum += chunks_of(b);
+  all_incl[tid] = sum;
+  full_incl[tid] = sum - (hi - lo);
   __syncthreads();
-  // Hillis-Steele inclusive scan over 256 partial sums
+  // Hillis-Steele inclusive scans over the 256 segment sums
   for (int off = 1; off < 256; off <<= 1) {
-    int32_t v = tid >= off ? part[tid - off] : 0;
+    const int32_t va = tid >= off ? all_incl[tid - off] : 0;
+    const int32_t vf = tid >= off ? full_incl[tid - off] : 0;
     __syncthreads();
-    part[tid] += v;
+    all_incl[tid] += va;
+    full_incl[tid] += vf;
     __syncthreads();
   }
-  int32_t run = part[tid] - sum;
-  for (int b = lo; b < hi; ++b) {
-    cu_chunks[b] = run;
-    const int32_t L = min(kv_lens[b], max_len);
-    run += L > 0 ? (L + chunk - 1) / chunk : 1;
-  }
-  const int32_t total = part[255];
-  if (tid == 0) {
-    cu_chunks[batch] = total;
-    hdr->total_items = total;
-  }
-  __syncthreads();  // cu_chunks written by this workgroup is visible to it
-  const int64_t n = total < max_items ? total : max_items;
-  for (int64_t i = tid; i < n; i += 256) {
-    int a = 0, z = batch;  // largest a with cu_chunks[a] <= i
-    while (z - a > 1) {
-      const int mid = (a + z) >> 1;
-      if (cu_chunks[mid] <= i) a = mid; else z = mid;
+  const int32_t total = all_incl[255];
+  const int32_t total_full = full_incl[255];
+  if (blockIdx.x == 0) {
+    int32_t run = all_incl[tid] - sum;
+    for (int b = lo; b < hi; ++b) {
+      cu_chunks[b] = run;
+      run += chunks_of(b);
     }
-    items[i] = make_int4(a, static_cast<int>(i - cu_chunks[a]), min(kv_lens[a], max_len), 0);
+    if (tid == 0) {
+      cu_chunks[batch] = total;
+      hdr->total_items = total;
+    }
+  }
+  const int64_t n = total < max_items ? total : max_items;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + tid; i < n; i += static_cast<int64_t>(gridDim.x) * 256) {
+    int b, c, slot;
+    if (i < total_full) {
+      // segment with full_excl[seg] <= i < full_incl[seg]
+      int a = 0, z = 255;
+      while (a < z) {
+        const int mid = (a + z) >> 1;
+        if (full_incl[mid] > i) z = mid; else a = mid + 1;
+      }
+      int32_t f = a ? full_incl[a - 1] : 0;   // full chunks before request b
+      int32_t s = a ? all_incl[a - 1] : 0;    // all chunks before request b
+      b = a * per;
+      for (;; ++b) {                          // ends inside the segment: it holds item i
+        const int nch = chunks_of(b);
+        if (i < f + nch - 1) break;
+        f += nch - 1;
+        s += nch;
+      }
+      c = static_cast<int>(i - f);
+      slot = s + c;
+    } else {
+      b = static_cast<int>(i - total_full);   // the last chunk of request b
+      const int seg = b / per;
+      int32_t s = seg ? all_incl[seg - 1] : 0;
+      for (int r = seg * per; r < b; ++r) s += chunks_of(r);
+      c = chunks_of(b) - 1;
+      slot = s + c;
+    }
+    items[i] = make_int4(b, c, min(kv_lens[b], max_len), slot);
   }
 }
 
@@ -441,6 +477,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
     slot = static_cast<int>(w & 0x3FFu);
   } else if (!a.direct) {
     it = a.items[item];
+    slot = it.w;
   }
   const int b = it.x;
   const int tid = threadIdx.x;
@@ -758,6 +795,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
     slot = static_cast<int>(w & 0x3FFu);
   } else if (!a.direct) {
     it = a.items[item];
+    slot = it.w;
   }
   const int b = it.x;
   const int tid = threadIdx.x;
@@ -1210,7 +1248,9 @@ AttnArgs make_args(const as_attn_params& p, const Checked& ck, const void* q, co
 
 as_status run_plan(const as_attn_params& p, const Checked& ck, const int32_t* lens, char* ws,
                    hipStream_t s) {
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, lens, p.batch, ck.chunk,
+  const int64_t wgs = (ck.w.max_items + 2047) / 2048;
+  hipLaunchKernelGGL(plan_kernel, dim3(static_cast<unsigned>(wgs < 1 ? 1 : wgs > 32 ? 32 : wgs)), dim3(256), 0, s,
+                     lens, p.batch, ck.chunk,
                      p.max_blocks_per_seq * kBlock,
                      reinterpret_cast<PlanHeader*>(ws), reinterpret_cast<int32_t*>(ws + ck.w.cu_off),
                      reinterpret_cast<int4*>(ws + ck.w.items_off), ck.w.max_items);

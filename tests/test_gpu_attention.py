@@ -242,3 +242,19 @@ def test_randomised_shapes_against_oracle(lib):
         assert np.isfinite(got).all(), (trial, dtype, D, Hkv, G, B, chunk)
         err = np.abs(got - ref).max()
         assert err <= TOL[dtype], (trial, dtype, D, Hkv, G, B, chunk, flags, err)
+
+
+@pytest.mark.parametrize("host_lens", [True, False])
+def test_device_built_plan_with_thousands_of_items(lib, host_lens):
+    """More items than the argument-borne plan holds (960): the plan kernel
+    builds the item table on several workgroups, full chunks first and the
+    requests' last chunks after them, and every partial lands in its request's
+    slots.  Lengths include exact multiples of the chunk and one-token requests."""
+    rng = np.random.default_rng(77)
+    lens = rng.integers(1, 700, 300).astype(np.int32)
+    lens[:6] = [64, 128, 1, 63, 65, 640]
+    pb = wl.make_paged_batch(lens, 2, 1, 64, dtype="fp32", seed=77, poison="nan", spare_blocks=1)
+    assert sum((int(l) + 63) // 64 for l in lens) > 960
+    _check(lib, pb, chunk_tokens=64, host_lens=host_lens)
+    pb16 = wl.make_paged_batch(lens, 8, 2, 128, dtype="bf16", seed=78, poison="nan")
+    _check(lib, pb16, chunk_tokens=64, host_lens=host_lens, out_dtype="fp32")   # matrix-core kernel
