@@ -531,6 +531,21 @@ def main():
                                                "its 1.5 GB working set is re-read back to back"}
         log(f"cfg1: {s1 * 1e6:.1f} us, {b1.bytes / s1 / 1e9:.0f} GB/s")
 
+        # ---------------- the same batch in fp16, the precision the paper runs its models in
+        pool1h = harness.make_device_pool(lens1, Hq, Hkv, D, dtype="fp16", seed=args.seed + 11)
+        b1h = harness.make_device_batches(pool1h, np.arange(len(lens1)), np.array([0, len(lens1)]), seed=7)[0]
+        p1h = als.attn_params(b1h.q, pool1h.k, b1h.block_table, b1h.out, chunk_tokens=args.chunk_tokens)
+
+        def attend1h():
+            als.decode_attention(b1h.q, pool1h.k, pool1h.v, b1h.block_table, b1h.kv_lens, b1h.out,
+                                 kv_lens_host=b1h.kv_lens_host, workspace=ws, params=p1h)
+        attend1h()
+        s1h = time_region(attend1h, 20, torch) / 20
+        result["cfg1_ragged_batch_fp16"] = {"us": round(s1h * 1e6, 1), "GBs": round(b1.bytes / s1h / 1e9, 0),
+                                            "note": "configs[1] with fp16 q/K/V/out (same bytes as bf16)"}
+        log(f"cfg1 fp16: {s1h * 1e6:.1f} us, {b1.bytes / s1h / 1e9:.0f} GB/s")
+        del pool1h, b1h
+
         # ---------------- one whole decode iteration of the 7B-shaped model's attention: 32 layers,
         # each with its own KV pool, the work plan built once and reused, eager and as one HIP graph
         layers = 32
