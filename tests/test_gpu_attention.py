@@ -258,3 +258,25 @@ def test_device_built_plan_with_thousands_of_items(lib, host_lens):
     _check(lib, pb, chunk_tokens=64, host_lens=host_lens)
     pb16 = wl.make_paged_batch(lens, 8, 2, 128, dtype="bf16", seed=78, poison="nan")
     _check(lib, pb16, chunk_tokens=64, host_lens=host_lens, out_dtype="fp32")   # matrix-core kernel
+
+
+def test_more_requests_than_the_inline_plan_holds_none_split(lib):
+    """1500 short requests, one chunk each: no plan at all (item i is request
+    i), a grid that is not a multiple of the XCD interleave, fp32 and bf16."""
+    rng = np.random.default_rng(91)
+    lens = rng.integers(1, 100, 1500).astype(np.int32)
+    pb = wl.make_paged_batch(lens, 2, 2, 64, dtype="fp32", seed=91, poison="nan", spare_blocks=1)
+    _check(lib, pb)
+    pb = wl.make_paged_batch(lens[:1111], 3, 1, 128, dtype="bf16", seed=92, poison="big")
+    _check(lib, pb, out_dtype="fp32")
+
+
+def test_one_very_long_request(lib):
+    """A single request far longer than the largest chunk (4096 tokens): 18
+    chunks of 64 tiles per wave, merged by the combine kernel; ragged tail."""
+    lens = np.array([70003], dtype=np.int32)
+    pb = wl.make_paged_batch(lens, 2, 2, 128, dtype="bf16", seed=93, poison="nan", spare_blocks=1)
+    _check(lib, pb, out_dtype="fp32")
+    _check(lib, pb, out_dtype="fp32", chunk_tokens=4096)
+    pb = wl.make_paged_batch(lens, 8, 1, 128, dtype="bf16", seed=94, poison="nan")     # matrix-core kernel
+    _check(lib, pb, out_dtype="fp32")
