@@ -11,9 +11,11 @@
 // tokens.  One workgroup (4 wavefronts) handles one (request, chunk, KV head)
 // item; items of all requests are flattened into one list so that the time of
 // a launch follows the total token count of the batch, not batch * longest
-// request.  The plan kernel builds that list on the device from kv_lens.
-// Chunks of one request are merged exactly afterwards (combine kernel); a
-// request that fits one chunk is finished by its workgroup directly.
+// request.  The list is built on the host and travels in the kernel arguments
+// when the host knows the lengths and it is short enough, otherwise a plan
+// kernel builds it on the device from kv_lens; either way long items run
+// first.  Chunks of one request are merged exactly afterwards (combine
+// kernel); a request that fits one chunk is finished by its workgroup directly.
 //
 // Inside a workgroup.  A tile is one 16-token block of one KV head: a
 // contiguous [16][D] slab.  A wavefront owns every 4th tile of the chunk.
@@ -1074,15 +1076,16 @@ __global__ __launch_bounds__(256) void sweep_fold_kernel(const uint32_t* __restr
 // ------------------------------------------------------------------ host side
 int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
   if (p.chunk_tokens > 0) return p.chunk_tokens;
-  // Long chunks amortise a workgroup's start-up (dependent loads of the item,
-  // the block ids and the first tile) and its merge; short chunks shorten the
-  // tail of the launch, where the last workgroups run next to idle compute
-  // units.  With a per-item overhead worth o tokens, S concurrently resident
-  // workgroups and a tail of about half a chunk, the cost
-  //   o * (T / chunk) / S + chunk / 2          (T = tokens * KV heads)
-  // is smallest at chunk = sqrt(2 o T / S); o ~ 128 tokens and S ~ 1024 were
-  // fitted to sweeps on MI355X (optimum ~900 tokens for a 90 k-token ragged MHA
-  // batch, ~2-4 k tokens for 0.6-2.4 M-token batches).
+  // Long chunks amortise what a workgroup pays once (its start-up, its merge
+  // and above all the stores of its result, which cost far more than their
+  // bytes next to a saturated read stream); short chunks shorten the tail of
+  // the launch, where the last workgroups run next to idle compute units.
+  // With a per-item overhead worth o tokens, S concurrently resident
+  // workgroups and a tail that grows with the chunk, the cost
+  //   o * (T / chunk) / S + tail(chunk)          (T = tokens * KV heads)
+  // is smallest at chunk = sqrt(k T).  Because items run longest-first the
+  // tail term is small; sweeps on MI355X put k at 1.5 (optimum ~2048 tokens
+  // for a 90 k-token ragged MHA batch, the 4096 maximum from ~110 k tokens).
   const double t = static_cast<double>(total_tokens) * p.num_kv_heads;
   // the grouped-query (matrix-core) kernel merges and writes up to 16 heads
   // per item: its per-item overhead is about 4x, so its best chunk about 2x
