@@ -627,7 +627,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
 // cores; the K/V stream, the work split and the merge stay as they are.
 //
 //   S^T[token][head] = K_tile[16 x 128] . Q^T[128 x 16]      4 x mfma 16x16x32
-//   O^T[dim][head]  += V_tile^T[128 x 16] . P^T[16 x 16]     8 x mfma 16x16x16
+//   O^T[dim][head]  += V_tile^T[128 x 16] . P^T[16 x 16]     2 x 8 x mfma 16x16x16
 //
 // Operand layouts (lane l, c = l % 16, r = l / 16):
 //  * A operand of a 16x16x32 MFMA wants lane l to hold 8 consecutive
@@ -643,20 +643,21 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
 //  * The result S^T has the head on c and tokens on (r, i): a lane owns ONE
 //    head, so the online softmax costs the same for any G <= 16.
 //  * P^T (B operand of the second MFMA) is exactly what the lane computed:
-//    probabilities of its 4 tokens for head c, rounded to the element type.
+//    probabilities of its 4 tokens for head c, as two terms hi + lo in the
+//    element type (two MFMAs per accumulator), so that the weights keep 16 or
+//    more significant bits instead of the 8 of a single bf16.
 //  * V needs no LDS: the lane's four loads hold, for each of its 8 dimensions,
 //    the 4 tokens (4i+r) -- the A operand (row = dimension 8c+e, 4 contraction
 //    values) once the 16-bit halves are gathered with v_perm.  Output register
 //    i of accumulator e is dimension 32r+8i+e of head c: the lane that owns a
 //    head's softmax state also owns that head's outputs, so rescaling is
 //    lane-local.
-// The sum l is accumulated from the rounded probabilities, so numerator and
-// denominator use the same weights.
+// The sum l is accumulated from the fp32 probabilities.
 constexpr int kLdsRow = 272;                    // 256 B of a K row + 16 B pad
 constexpr int kLdsKTile = kBlock * kLdsRow;     // per wave
 constexpr int kMfmaHeads = 16;
 
-// The two 16-bit element types differ only in the MFMA opcodes and in how the
+// The two 16-bit element types differ only in the MFMA opcodes and in how
 // probabilities are rounded to the element type and widened back.
 template <typename T> struct Mfma;
 template <> struct Mfma<bf16_t> {
@@ -673,7 +674,8 @@ template <> struct Mfma<bf16_t> {
     const f32x2 f = {a, b};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
   }
-  __device__ static __forceinline__ float pair_sum(uint32_t w) { return bf16_lo(w) + bf16_hi(w); }
+  __device__ static __forceinline__ float first(uint32_t w) { return bf16_lo(w); }
+  __device__ static __forceinline__ float second(uint32_t w) { return bf16_hi(w); }
 };
 template <> struct Mfma<f16_t> {
   __device__ static __forceinline__ f32x4 qk(const u32x4& k, const u32x4& q, const f32x4& s) {
@@ -688,9 +690,11 @@ template <> struct Mfma<f16_t> {
     const f32x2 f = {a, b};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, h16x2_t));
   }
-  __device__ static __forceinline__ float pair_sum(uint32_t w) {
-    const f32x2 f = __builtin_convertvector(__builtin_bit_cast(h16x2_t, w), f32x2);
-    return f.x + f.y;
+  __device__ static __forceinline__ float first(uint32_t w) {
+    return __builtin_convertvector(__builtin_bit_cast(h16x2_t, w), f32x2).x;
+  }
+  __device__ static __forceinline__ float second(uint32_t w) {
+    return __builtin_convertvector(__builtin_bit_cast(h16x2_t, w), f32x2).y;
   }
 };
 
@@ -735,7 +739,12 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
   }
   const uint32_t w01 = Mfma<T>::pack(p[0], p[1]);
   const uint32_t w23 = Mfma<T>::pack(p[2], p[3]);
-  const float psum = Mfma<T>::pair_sum(w01) + Mfma<T>::pair_sum(w23);
+  // second term of the two-term representation p = hi + lo (each in the
+  // element type): the matrix cores have cycles to spare next to the K/V
+  // stream, and two terms carry 16 (bf16) or 22 (fp16) bits of the fp32 weight
+  const uint32_t x01 = Mfma<T>::pack(p[0] - Mfma<T>::first(w01), p[1] - Mfma<T>::second(w01));
+  const uint32_t x23 = Mfma<T>::pack(p[2] - Mfma<T>::first(w23), p[3] - Mfma<T>::second(w23));
+  const float psum = (p[0] + p[1]) + (p[2] + p[3]);
   l_run = fmaf(l_run, alpha, psum);
   m_run = m_new;
   if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
@@ -743,6 +752,7 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
     for (int e = 0; e < 8; ++e) acc[e] *= alpha;
   }
   const u32x2 pB = {w01, w23};
+  const u32x2 pB2 = {x01, x23};
 
   // V: gather the 16-bit halves of the 4 tokens for each of the lane's 8 dims
   u32x4 v0 = vr[0], v1 = vr[1], v2 = vr[2], v3 = vr[3];
@@ -763,6 +773,8 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
                       __builtin_amdgcn_perm(a3[w], a2[w], 0x07060302u)};
     acc[2 * w] = Mfma<T>::pv(lo, pB, acc[2 * w]);
     acc[2 * w + 1] = Mfma<T>::pv(hi, pB, acc[2 * w + 1]);
+    acc[2 * w] = Mfma<T>::pv(lo, pB2, acc[2 * w]);
+    acc[2 * w + 1] = Mfma<T>::pv(hi, pB2, acc[2 * w + 1]);
   }
 }
 

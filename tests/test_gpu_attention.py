@@ -57,9 +57,9 @@ def test_result_independent_of_split(lib, dtype):
     from paper_2605_23389_amd import binding as als
     # the vector-ALU kernel keeps probabilities in fp32: the split only changes
     # the summation order.  The matrix-core kernel (bf16, group of 4 here)
-    # rounds probabilities to bf16 relative to each chunk's own maximum, so
-    # different splits differ by that rounding (still inside the tolerance).
-    for flags, bound in ((als.ATTN_NO_MFMA, 2e-6 if dtype == "fp32" else 1e-5), (0, 5e-3)):
+    # carries probabilities as two bf16 terms relative to each chunk's own
+    # maximum, so different splits differ by that (16-bit) rounding.
+    for flags, bound in ((als.ATTN_NO_MFMA, 2e-6 if dtype == "fp32" else 1e-5), (0, 5e-5)):
         outs = []
         for chunk in (16, 48, 112, 256, 1024, 4096, 0):
             got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=chunk, dev=dev, flags=flags)
@@ -193,7 +193,9 @@ def test_matrix_core_path_matches_oracle_and_vector_path(lib, Hq, Hkv):
         for chunk in (0, 64, 512):
             got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=chunk, dev=dev)
             assert np.isfinite(got).all()
-            assert np.abs(got - ref).max() <= TOL["bf16"]
+            # far inside the bf16 budget: the kernel's own error is that of
+            # 16-bit weights and fp32 accumulation
+            assert np.abs(got - ref).max() <= 1e-4
         valu = run_attention(lib, pb, out_dtype="fp32", dev=dev, flags=als.ATTN_NO_MFMA)
         assert np.abs(valu - ref).max() <= TOL["bf16"]
 
