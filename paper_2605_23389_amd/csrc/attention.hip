@@ -785,7 +785,11 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   constexpr size_t kSlabBytes = static_cast<size_t>(kBlock) * D * 2;
   // the K transpose tiles (loop) and the cross-wave merge buffers (epilogue)
   // share one allocation; a barrier separates the two uses
-  constexpr int kMergeBytes = kWaves * kMfmaHeads * D * 4;
+  // merge rows are padded by 4 floats: a lane's 8 x 128-bit writes of its 32
+  // consecutive output dimensions then fall on distinct banks across the 8
+  // lanes (neighbouring heads) that one LDS cycle serves
+  constexpr int kMergeRow = D + 4;
+  constexpr int kMergeBytes = kWaves * kMfmaHeads * kMergeRow * 4;
   __shared__ __attribute__((aligned(16))) char smem[kMergeBytes];
   __shared__ float sm_m[kWaves][kMfmaHeads];
   __shared__ float sm_l[kWaves][kMfmaHeads];
@@ -905,14 +909,18 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   l_run += __shfl_xor(l_run, 32);
 
   __syncthreads();  // every wave is done with its K tile: the buffer becomes merge space
-  float* sm_o = reinterpret_cast<float*>(smem);  // [wave][head][D]
+  float* sm_o = reinterpret_cast<float*>(smem);  // [wave][head][kMergeRow]
   if (col < G) {
     if (rg == 0) { sm_m[wave][col] = m_run; sm_l[wave][col] = l_run; }
+    // register i of accumulator e is dimension 32*rg + 8*i + e: the lane owns
+    // 32 consecutive dimensions of head `col`, written as 8 float4
+    float* row = sm_o + (wave * kMfmaHeads + col) * kMergeRow + 32 * rg;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float v[4] = {acc[e].x, acc[e].y, acc[e].z, acc[e].w};
-#pragma unroll
-      for (int i = 0; i < 4; ++i) sm_o[(wave * kMfmaHeads + col) * D + 32 * rg + 8 * i + e] = v[i];
+    for (int i = 0; i < 4; ++i) {
+      const f32x4 lo4 = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+      const f32x4 hi4 = {acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
+      *reinterpret_cast<f32x4*>(row + 8 * i) = lo4;
+      *reinterpret_cast<f32x4*>(row + 8 * i + 4) = hi4;
     }
   }
   __syncthreads();
@@ -928,7 +936,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
     for (int w = 0; w < kWaves; ++w) {
       const float f = fast_exp2((sm_m[w][g] - M) * c);
       l = fmaf(sm_l[w][g], f, l);
-      o = fmaf(sm_o[(w * kMfmaHeads + g) * D + d], f, o);
+      o = fmaf(sm_o[(w * kMfmaHeads + g) * kMergeRow + d], f, o);
     }
     const int hq = hg * G + g;
     if (single) {
