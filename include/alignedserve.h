@@ -184,6 +184,7 @@ size_t as_decode_attention_workspace(const as_attn_params* p, int64_t total_kv_t
  *              bytes, 256-byte aligned; its contents are only meaningful to
  *              the library (plan + split-KV partials) and may be reused by
  *              the next call.
+ * q, k_blocks, v_blocks and out must be 16-byte aligned (AS_EINVAL otherwise).
  * Inputs are read-only; out and workspace are the only memory written.
  * Device-side contents of block_table are not validated on the hot path;
  * ids are clamped into the pool so that a bad id yields a wrong result, not

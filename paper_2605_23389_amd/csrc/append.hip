@@ -50,6 +50,9 @@ extern "C" as_status as_kv_append(const void* k_new, const void* v_new, void* k_
                                   void* hip_stream) {
   if (!k_new || !v_new || !k_blocks || !v_blocks || !block_table || !kv_lens || !p)
     return als::fail(AS_EINVAL, "as_kv_append: a required pointer is null");
+  if ((reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new) |
+       reinterpret_cast<uintptr_t>(k_blocks) | reinterpret_cast<uintptr_t>(v_blocks)) % 16)
+    return als::fail(AS_EINVAL, "as_kv_append: k_new, v_new, k_blocks and v_blocks must be 16-byte aligned");
   if (p->batch < 1 || p->num_kv_heads < 1 || p->num_blocks < 1 || p->max_blocks_per_seq < 1)
     return als::fail(AS_EINVAL, "as_kv_append: batch, num_kv_heads, num_blocks, max_blocks_per_seq must be positive");
   if (p->block_size != 16) return als::fail(AS_EUNSUPPORTED, "as_kv_append: block_size %d (only 16 is built)", p->block_size);

@@ -1302,6 +1302,12 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
                                          size_t workspace_bytes, void* hip_stream) {
   if (!q || !k_blocks || !v_blocks || !block_table || !kv_lens || !out || !workspace)
     return als::fail(AS_EINVAL, "as_decode_attention: a required pointer is null");
+  // the kernels move q, K, V and the result with 128-bit accesses
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_blocks) |
+       reinterpret_cast<uintptr_t>(v_blocks) | reinterpret_cast<uintptr_t>(out)) % 16)
+    return als::fail(AS_EINVAL, "as_decode_attention: q, k_blocks, v_blocks and out must be 16-byte aligned");
+  if ((reinterpret_cast<uintptr_t>(block_table) | reinterpret_cast<uintptr_t>(kv_lens)) % 4)
+    return als::fail(AS_EINVAL, "as_decode_attention: block_table and kv_lens must be 4-byte aligned");
   Checked ck;
   as_status st = validate("as_decode_attention", p, kv_lens_host, workspace_bytes, workspace, &ck);
   if (st != AS_OK) return st;
@@ -1378,6 +1384,11 @@ extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks
                                       size_t workspace_bytes, void* hip_stream) {
   if (!k_blocks || !v_blocks || !block_table || !kv_lens || !checksum || !workspace)
     return als::fail(AS_EINVAL, "as_kv_read_sweep: a required pointer is null");
+  if ((reinterpret_cast<uintptr_t>(k_blocks) | reinterpret_cast<uintptr_t>(v_blocks)) % 16)
+    return als::fail(AS_EINVAL, "as_kv_read_sweep: k_blocks and v_blocks must be 16-byte aligned");
+  if ((reinterpret_cast<uintptr_t>(block_table) | reinterpret_cast<uintptr_t>(kv_lens) |
+       reinterpret_cast<uintptr_t>(checksum)) % 4)
+    return als::fail(AS_EINVAL, "as_kv_read_sweep: block_table, kv_lens and checksum must be 4-byte aligned");
   Checked ck;
   as_status st = validate("as_kv_read_sweep", p, kv_lens_host, workspace_bytes, workspace, &ck);
   if (st != AS_OK) return st;

@@ -129,6 +129,13 @@ as_status move_blocks(const char* what, char* host_k, char* host_v, const int64_
                     (policy == AS_STAGE_AUTO &&
                      static_cast<size_t>(m) * block_bytes < static_cast<size_t>(runs) * kAutoRunBytes);
   char *hk_dev = nullptr, *hv_dev = nullptr;
+  if (use_kernel && (reinterpret_cast<uintptr_t>(host_k) | reinterpret_cast<uintptr_t>(host_v) |
+                     reinterpret_cast<uintptr_t>(dev_k) | reinterpret_cast<uintptr_t>(dev_v)) % 16) {
+    // the kernel moves 128-bit words; pools at odd addresses keep the DMA path
+    if (policy == AS_STAGE_KERNEL)
+      return als::fail(AS_EINVAL, "%s: pools must be 16-byte aligned for the copy kernel", what);
+    use_kernel = false;
+  }
   if (use_kernel) {
     // the address the device uses for the pinned host pool; memory that is
     // pinned but not mapped into the device's address space keeps the DMA path

@@ -119,6 +119,8 @@ def test_decode_attention_argument_errors_before_any_gpu_work(lib):
     assert "kv_lens_host[1]" in handle.as_last_error().decode()
     assert call(_params(), ws_bytes=16) == als.AS_EWORKSPACE
     assert call(_params(), ws=C.c_void_p(0x10010)) == als.AS_EINVAL
+    assert call(_params(), q=C.c_void_p(0x1008)) == als.AS_EINVAL       # not 16-byte aligned
+    assert "16-byte aligned" in handle.as_last_error().decode()
 
 
 def test_workspace_size_query(lib):
