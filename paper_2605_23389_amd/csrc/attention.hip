@@ -1236,7 +1236,11 @@ void launch_attn(int G, dim3 grid, hipStream_t s, const AttnArgs& a, const Inlin
   switch (G) {
     case 1: hipLaunchKernelGGL((attn_kernel<T, D, 1>), grid, dim3(kThreads), 0, s, a, ip); break;
     case 2: hipLaunchKernelGGL((attn_kernel<T, D, 2>), grid, dim3(kThreads), 0, s, a, ip); break;
+    case 3: hipLaunchKernelGGL((attn_kernel<T, D, 3>), grid, dim3(kThreads), 0, s, a, ip); break;
     case 4: hipLaunchKernelGGL((attn_kernel<T, D, 4>), grid, dim3(kThreads), 0, s, a, ip); break;
+    case 5: hipLaunchKernelGGL((attn_kernel<T, D, 5>), grid, dim3(kThreads), 0, s, a, ip); break;
+    case 6: hipLaunchKernelGGL((attn_kernel<T, D, 6>), grid, dim3(kThreads), 0, s, a, ip); break;
+    case 7: hipLaunchKernelGGL((attn_kernel<T, D, 7>), grid, dim3(kThreads), 0, s, a, ip); break;
     default: hipLaunchKernelGGL((attn_kernel<T, D, 8>), grid, dim3(kThreads), 0, s, a, ip); break;
   }
 }
@@ -1341,10 +1345,13 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
     else
       hipLaunchKernelGGL(attn_mfma_kernel<f16_t>, grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
   } else {
-    // query heads handled by one workgroup: the largest of 8, 4, 2, 1 that
-    // divides the GQA group; a group that is not a power of two up to 8 is
-    // covered by several workgroups reading the same KV head
-    const int G = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
+    // query heads handled by one workgroup: the largest divisor of the GQA
+    // group up to 8, so that one K/V read serves as many heads as possible;
+    // what is left of a wider group is covered by several workgroups reading
+    // the same KV head (a prime group above 8 by one workgroup per head)
+    int G = 1;
+    for (int d = 2; d <= 8; ++d)
+      if (group % d == 0) G = d;
     a.head_groups = p->num_q_heads / G;
     a.kv_div = group / G;
     const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
