@@ -185,6 +185,11 @@ size_t as_decode_attention_workspace(const as_attn_params* p, int64_t total_kv_t
  *              the library (plan + split-KV partials) and may be reused by
  *              the next call.
  * q, k_blocks, v_blocks and out must be 16-byte aligned (AS_EINVAL otherwise).
+ * Under HIP graph capture a call made with kv_lens_host bakes the work plan
+ * derived from those lengths into the captured launches: replay it only while
+ * the device lengths equal them.  A call without kv_lens_host plans on the
+ * device at every replay and follows kv_lens as it changes (up to
+ * max_blocks_per_seq * 16 tokens per request).
  * Inputs are read-only; out and workspace are the only memory written.
  * Device-side contents of block_table are not validated on the hot path;
  * ids are clamped into the pool so that a bad id yields a wrong result, not
