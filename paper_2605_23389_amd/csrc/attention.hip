@@ -100,13 +100,16 @@ WorkspaceLayout layout_for(const as_attn_params& p, int64_t max_items) {
 // travels in the kernel arguments, and calls without host lengths).  A request
 // of L tokens has n = ceil(L / chunk) chunks (one when L <= 0: it writes
 // zeros).  Order of execution: every full chunk first (request-major), then
-// each request's last chunk in request order, so that a launch ends on short
-// items.  An item's partial result goes to its canonical slot
-// cu_chunks[request] + chunk, cu_chunks = exclusive scan of n.
+// each request's last chunk from long to short (64 length classes, counting
+// sort), so that a launch ends on its smallest items.  An item's partial
+// result goes to its canonical slot cu_chunks[request] + chunk, cu_chunks =
+// exclusive scan of n.
 // Every workgroup repeats the two 256-entry scans in LDS (thread t covers
-// `per` consecutive requests) and fills its share of the table; the requests
-// inside a thread's segment are walked linearly.  Workgroup 0 also writes
-// cu_chunks and the header.
+// `per` consecutive requests) and fills its share of the full chunks; the
+// requests inside a thread's segment are walked linearly.  Workgroup 0 also
+// writes cu_chunks, the header and the last chunks (their order inside a
+// length class depends on the run, the results do not: every item owns its
+// slot).
 __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ kv_lens, int batch,
                                                    int chunk, int max_len, PlanHeader* __restrict__ hdr,
                                                    int32_t* __restrict__ cu_chunks,
@@ -149,35 +152,52 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ k
     }
   }
   const int64_t n = total < max_items ? total : max_items;
-  for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + tid; i < n; i += static_cast<int64_t>(gridDim.x) * 256) {
-    int b, c, slot;
-    if (i < total_full) {
-      // segment with full_excl[seg] <= i < full_incl[seg]
-      int a = 0, z = 255;
-      while (a < z) {
-        const int mid = (a + z) >> 1;
-        if (full_incl[mid] > i) z = mid; else a = mid + 1;
-      }
-      int32_t f = a ? full_incl[a - 1] : 0;   // full chunks before request b
-      int32_t s = a ? all_incl[a - 1] : 0;    // all chunks before request b
-      b = a * per;
-      for (;; ++b) {                          // ends inside the segment: it holds item i
-        const int nch = chunks_of(b);
-        if (i < f + nch - 1) break;
-        f += nch - 1;
-        s += nch;
-      }
-      c = static_cast<int>(i - f);
-      slot = s + c;
-    } else {
-      b = static_cast<int>(i - total_full);   // the last chunk of request b
-      const int seg = b / per;
-      int32_t s = seg ? all_incl[seg - 1] : 0;
-      for (int r = seg * per; r < b; ++r) s += chunks_of(r);
-      c = chunks_of(b) - 1;
-      slot = s + c;
+  const int64_t n_full = total_full < n ? total_full : n;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + tid; i < n_full;
+       i += static_cast<int64_t>(gridDim.x) * 256) {
+    // segment with full_excl[seg] <= i < full_incl[seg]
+    int a = 0, z = 255;
+    while (a < z) {
+      const int mid = (a + z) >> 1;
+      if (full_incl[mid] > i) z = mid; else a = mid + 1;
     }
-    items[i] = make_int4(b, c, min(kv_lens[b], max_len), slot);
+    int32_t f = a ? full_incl[a - 1] : 0;   // full chunks before request b
+    int32_t s = a ? all_incl[a - 1] : 0;    // all chunks before request b
+    int b = a * per;
+    for (;; ++b) {                          // ends inside the segment: it holds item i
+      const int nch = chunks_of(b);
+      if (i < f + nch - 1) break;
+      f += nch - 1;
+      s += nch;
+    }
+    const int c = static_cast<int>(i - f);
+    items[i] = make_int4(b, c, min(kv_lens[b], max_len), s + c);
+  }
+  if (blockIdx.x != 0) return;
+  // last chunks: class 0 holds the longest (tokens in the chunk from chunk down
+  // to chunk * 63/64 + 1), class 63 the shortest and the empty requests
+  __shared__ int32_t cls_count[64];
+  __shared__ int32_t cls_next[64];
+  auto class_of = [&](int b, int nch) {
+    const int32_t L = min(kv_lens[b], max_len);
+    const int rem = L > 0 ? L - (nch - 1) * chunk : 1;   // 1 .. chunk
+    return 63 - min(63, (rem - 1) * 64 / chunk);
+  };
+  if (tid < 64) cls_count[tid] = 0;
+  __syncthreads();
+  for (int b = lo; b < hi; ++b) atomicAdd(&cls_count[class_of(b, chunks_of(b))], 1);
+  __syncthreads();
+  if (tid == 0) {
+    int32_t run = 0;
+    for (int k = 0; k < 64; ++k) { cls_next[k] = run; run += cls_count[k]; }
+  }
+  __syncthreads();
+  int32_t s = all_incl[tid] - sum;            // all chunks before this thread's segment
+  for (int b = lo; b < hi; ++b) {
+    const int nch = chunks_of(b);
+    const int64_t i = total_full + atomicAdd(&cls_next[class_of(b, nch)], 1);
+    if (i < n) items[i] = make_int4(b, nch - 1, min(kv_lens[b], max_len), s + nch - 1);
+    s += nch;
   }
 }
 
