@@ -1114,6 +1114,30 @@ __global__ __launch_bounds__(256) void sweep_fold_kernel(const uint32_t* __restr
 }
 
 // ------------------------------------------------------------------ host side
+// Which kernel serves these parameters and how many query heads one workgroup
+// takes.  Matrix-core path: 16-bit inputs, D = 128, grouped-query shapes where
+// the vector-ALU kernel is bound by its own arithmetic; one workgroup takes up
+// to 16 heads of a group, wider groups are cut into 16s or 8s.  Vector-ALU
+// path: the largest divisor of the group up to 8, so that one K/V read serves
+// as many heads as possible; what is left of a wider group is covered by
+// several workgroups reading the same KV head.
+struct KernelChoice {
+  bool mfma;
+  int heads;  // query heads per workgroup
+};
+KernelChoice choose_kernel(const as_attn_params& p) {
+  const int group = p.num_q_heads / p.num_kv_heads;
+  if (p.dtype != AS_DTYPE_F32 && p.head_dim == 128 && group >= 4 && !(p.flags & AS_ATTN_NO_MFMA)) {
+    if (group <= 16) return {true, group};
+    if (group % 16 == 0) return {true, 16};
+    if (group % 8 == 0) return {true, 8};
+  }
+  int g = 1;
+  for (int d = 2; d <= 8; ++d)
+    if (group % d == 0) g = d;
+  return {false, g};
+}
+
 int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
   if (p.chunk_tokens > 0) return p.chunk_tokens;
   // Long chunks amortise what a workgroup pays once (its start-up, its merge
@@ -1129,8 +1153,7 @@ int pick_chunk(const as_attn_params& p, int64_t total_tokens) {
   const double t = static_cast<double>(total_tokens) * p.num_kv_heads;
   // the grouped-query (matrix-core) kernel merges and writes up to 16 heads
   // per item: its per-item overhead is about 4x, so its best chunk about 2x
-  const int group = p.num_q_heads / p.num_kv_heads;
-  const bool wide = p.dtype != AS_DTYPE_F32 && p.head_dim == 128 && group >= 4;
+  const bool wide = choose_kernel(p).mfma;
   int chunk = static_cast<int>(std::sqrt(wide ? 6.0 * t : 1.5 * t));
   chunk = (chunk + 63) / 64 * 64;
   if (chunk < 256) chunk = 256;
@@ -1194,9 +1217,26 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
     int max_len = 0;
     for (int b = 0; b < p->batch; ++b) max_len = kv_lens_host[b] > max_len ? kv_lens_host[b] : max_len;
     const bool aligned = static_cast<double>(max_len) * p->batch <= 1.5 * static_cast<double>(total);
-    if (out->chunk < max_len &&
-        (max_len <= 1024 || (max_len <= kMaxChunk && (max_len <= 2 * out->chunk || aligned))))
-      out->chunk = (max_len + kBlock - 1) / kBlock * kBlock;
+    // ... provided the requests alone make enough workgroups: with fewer
+    // than one per compute unit a launch is bound by what a single workgroup
+    // can stream, and splitting pays.  Such small launches get chunks sized
+    // for about one workgroup per compute unit (fewer for the matrix-core
+    // kernel, whose items cost more), but not below 512 tokens; fitted to
+    // sweeps over 1-16 requests of 512 to 131072 tokens.
+    const KernelChoice kc = choose_kernel(*p);
+    const int64_t head_groups = p->num_q_heads / kc.heads;
+    if (p->batch * head_groups >= 256) {
+      if (out->chunk < max_len &&
+          (max_len <= 1024 || (max_len <= kMaxChunk && (max_len <= 2 * out->chunk || aligned))))
+        out->chunk = (max_len + kBlock - 1) / kBlock * kBlock;
+    } else {
+      int64_t par = total * head_groups / (kc.mfma ? 192 : 256);
+      par = (par + 63) / 64 * 64;
+      if (par < 512) par = 512;
+      if (par > kMaxChunk) par = kMaxChunk;
+      out->chunk = static_cast<int>(par);
+      if (out->chunk > max_len) out->chunk = (max_len + kBlock - 1) / kBlock * kBlock;
+    }
   }
   out->exact = kv_lens_host != nullptr;
   out->any_split = true;
@@ -1347,15 +1387,8 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
   AttnArgs a = make_args(*p, ck, q, k_blocks, v_blocks, block_table, kv_lens, out, ws);
 
   const int group = p->num_q_heads / p->num_kv_heads;
-  // Matrix-core path: 16-bit inputs, D = 128, grouped-query shapes where the vector-ALU
-  // kernel is bound by its own arithmetic.  One workgroup takes up to 16 heads
-  // of a group; wider groups are cut into 16s or 8s.
-  int mfma_heads = 0;
-  if (p->dtype != AS_DTYPE_F32 && p->head_dim == 128 && group >= 4 && !(p->flags & AS_ATTN_NO_MFMA)) {
-    if (group <= 16) mfma_heads = group;
-    else if (group % 16 == 0) mfma_heads = 16;
-    else if (group % 8 == 0) mfma_heads = 8;
-  }
+  const KernelChoice kc = choose_kernel(*p);
+  const int mfma_heads = kc.mfma ? kc.heads : 0;
   if (mfma_heads) {
     a.head_groups = p->num_q_heads / mfma_heads;
     a.kv_div = group / mfma_heads;
@@ -1365,13 +1398,7 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
     else
       hipLaunchKernelGGL(attn_mfma_kernel<f16_t>, grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
   } else {
-    // query heads handled by one workgroup: the largest divisor of the GQA
-    // group up to 8, so that one K/V read serves as many heads as possible;
-    // what is left of a wider group is covered by several workgroups reading
-    // the same KV head (a prime group above 8 by one workgroup per head)
-    int G = 1;
-    for (int d = 2; d <= 8; ++d)
-      if (group % d == 0) G = d;
+    const int G = kc.heads;
     a.head_groups = p->num_q_heads / G;
     a.kv_div = group / G;
     const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
