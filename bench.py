@@ -282,6 +282,8 @@ def main():
     ap.add_argument("--skip-extra", action="store_true",
                     help="only the headline pass (used for profiling runs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--only-pipeline", action="store_true",
+                    help="profiling aid: run only the scaled configs[4] staging/attention pipeline and print its line")
     ap.add_argument("--only-cfg3", action="store_true",
                     help="profiling aid: run only the GQA long-context batch (configs[3]) and print its line")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -301,6 +303,10 @@ def main():
     als.load()
     torch.cuda.set_device(0)
     dev_name = torch.cuda.get_device_name(0)
+    if args.only_pipeline:
+        print(json.dumps({"workload": "configs[4] host-resident KV pipeline (scaled)",
+                          **pipeline_leg(args, torch, als, harness, traffic, wl, log)}), flush=True)
+        return
     if args.only_cfg3:
         if args.copy_calibration:
             src = torch.empty(1 << 31, dtype=torch.uint8, device="cuda").fill_(1)
