@@ -1,6 +1,9 @@
 """Helpers shared by the GPU parity tests: move a seeded PagedBatch to the
-device, run the C-ABI attention on it, and fetch the result as float64."""
+device, run the C-ABI attention on it, fetch the result as float64, and
+compare it with the oracle under the bounds of tests/parity_bounds.py."""
 import numpy as np
+
+from tests import parity_bounds as pbnd
 
 
 def to_device(pb):
@@ -34,3 +37,12 @@ def oracle_out(pb, scale=None):
     from oracle import attention as oa
     return oa.decode_attention(pb.as_float("q"), pb.as_float("k_blocks"), pb.as_float("v_blocks"),
                                pb.block_table, pb.kv_lens, scale=scale)
+
+
+def check_parity(got, ref, pb, out_dtype=None, flags=0, what=""):
+    """Tight (kernel-arithmetic) bound and the contract, for a result of the
+    library's own kernel choice on this batch's shape."""
+    Hq, D = pb.q.shape[1], pb.q.shape[2]
+    Hkv = pb.k_blocks.shape[1]
+    mc = pbnd.uses_matrix_core(pb.dtype, D, Hq, Hkv, no_mfma=bool(flags & 2))
+    return pbnd.assert_parity(got, ref, pb.dtype, out_dtype or pb.dtype, mc, what)

@@ -1,13 +1,17 @@
 """GPU parity: the HIP decode attention (through the C ABI) against the fp64
 oracle, element by element on the same seeded inputs.
 
-Tolerances (max-abs over all elements): 1e-5 for fp32 inputs, 1.5e-2 for bf16
-inputs with fp32 accumulation."""
+Tolerances: the contract is a max-abs error of 1e-5 for fp32 inputs and 1.5e-2
+for bf16 inputs with fp32 accumulation; every comparison here also asserts the
+bound the kernels' arithmetic gives (tests/parity_bounds.py: 1e-5 for the
+vector-ALU kernel and 1e-4 for the matrix-core kernel with fp32 output, plus
+half an ulp of the output format for 16-bit output), because the absolute
+1.5e-2 cannot fail on long requests."""
 import numpy as np
 import pytest
 
 from paper_2605_23389_amd import workloads as wl
-from tests.gpu_util import oracle_out, run_attention, to_device
+from tests.gpu_util import check_parity, oracle_out, run_attention, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -17,10 +21,7 @@ TOL = {"fp32": 1e-5, "bf16": 1.5e-2}
 def _check(lib, pb, **kw):
     ref = oracle_out(pb, scale=kw.get("scale") or None)
     got = run_attention(lib, pb, **kw)
-    assert np.isfinite(got).all()
-    err = np.abs(got - ref).max()
-    assert err <= TOL[pb.dtype], f"max-abs err {err:.3e}"
-    return err
+    return check_parity(got, ref, pb, out_dtype=kw.get("out_dtype"), flags=kw.get("flags", 0))
 
 
 def test_tiny_config_fp32(lib):
@@ -63,7 +64,7 @@ def test_result_independent_of_split(lib, dtype):
         outs = []
         for chunk in (16, 48, 112, 256, 1024, 4096, 0):
             got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=chunk, dev=dev, flags=flags)
-            assert np.abs(got - ref).max() <= TOL[dtype]
+            check_parity(got, ref, pb, out_dtype="fp32", flags=flags)
             outs.append(got)
         spread = max(np.abs(o - outs[0]).max() for o in outs)
         assert spread <= bound, f"spread {spread:.3e} (flags {flags})"
@@ -75,7 +76,7 @@ def test_without_host_lens_and_plan_reuse(lib):
     pb = wl.make_paged_batch(lens, 4, 4, 128, dtype="bf16", seed=8, poison="nan", spare_blocks=1)
     ref = oracle_out(pb)
     got = run_attention(lib, pb, out_dtype="fp32", host_lens=False, chunk_tokens=256)
-    assert np.abs(got - ref).max() <= TOL["bf16"]
+    check_parity(got, ref, pb, out_dtype="fp32")
     # second "layer" with the plan reused from a shared workspace
     import torch
     d = to_device(pb)
@@ -91,7 +92,7 @@ def test_without_host_lens_and_plan_reuse(lib):
                          workspace=ws, params=params)
     torch.cuda.synchronize()
     assert torch.equal(first, out)
-    assert np.abs(out.double().cpu().numpy() - ref).max() <= TOL["bf16"]
+    check_parity(out.double().cpu().numpy(), ref, pb, out_dtype="fp32")
 
 
 def test_single_token_returns_v_bitwise(lib):
@@ -192,12 +193,11 @@ def test_matrix_core_path_matches_oracle_and_vector_path(lib, Hq, Hkv):
         dev = to_device(pb)
         for chunk in (0, 64, 512):
             got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=chunk, dev=dev)
-            assert np.isfinite(got).all()
             # far inside the bf16 budget: the kernel's own error is that of
             # 16-bit weights and fp32 accumulation
-            assert np.abs(got - ref).max() <= 1e-4
+            check_parity(got, ref, pb, out_dtype="fp32")
         valu = run_attention(lib, pb, out_dtype="fp32", dev=dev, flags=als.ATTN_NO_MFMA)
-        assert np.abs(valu - ref).max() <= TOL["bf16"]
+        check_parity(valu, ref, pb, out_dtype="fp32", flags=als.ATTN_NO_MFMA)
 
 
 def test_matrix_core_path_one_hot_and_mean_limits(lib):
@@ -241,9 +241,8 @@ def test_randomised_shapes_against_oracle(lib):
         ref = oracle_out(pb)
         got = run_attention(lib, pb, out_dtype=out_dtype, chunk_tokens=chunk, flags=flags,
                             host_lens=bool(rng.integers(0, 2)))
-        assert np.isfinite(got).all(), (trial, dtype, D, Hkv, G, B, chunk)
-        err = np.abs(got - ref).max()
-        assert err <= TOL[dtype], (trial, dtype, D, Hkv, G, B, chunk, flags, err)
+        check_parity(got, ref, pb, out_dtype=out_dtype, flags=flags,
+                     what=str((trial, dtype, D, Hkv, G, B, chunk, flags)))
 
 
 @pytest.mark.parametrize("host_lens", [True, False])

@@ -3,7 +3,11 @@ times: the 1024-request, 31.6 GB MHA workload (aligned and random batches)
 and the GQA long-context batch.  The oracle cannot do whole batches at this
 size, so sampled (request, head) outputs are checked one by one, plus
 properties that hold at any size (every output finite; every request
-written)."""
+written).  Each workload runs with fp32 output under the bound the kernel's
+arithmetic gives (1e-5 vector-ALU, 1e-4 matrix-core: at these lengths the
+outputs are ~0.01 in magnitude, so the contract's absolute 1.5e-2 alone could
+not fail) and with the benchmark's bf16 output under that bound plus the
+output rounding."""
 import math
 
 import numpy as np
@@ -12,6 +16,7 @@ import pytest
 from oracle import attention as oa
 from paper_2605_23389_amd import harness
 from paper_2605_23389_amd import workloads as wl
+from tests import parity_bounds as pbnd
 
 pytestmark = pytest.mark.gpu
 
@@ -25,8 +30,10 @@ def _run(lib, pool, batch, ws=None):
     assert torch.isfinite(batch.out.float()).all()
 
 
-def _check_samples(pool, batch, samples, tol, G):
+def _check_samples(pool, batch, samples, G, outs):
+    """outs: {out_dtype name: output tensor} of runs on this batch."""
     D = pool.head_dim
+    mc = pbnd.uses_matrix_core("bf16", D, pool.num_q_heads, pool.num_kv_heads)
     worst = 0.0
     for (i, kvh) in samples:
         req = int(batch.members[i])
@@ -35,15 +42,31 @@ def _check_samples(pool, batch, samples, tol, G):
             hq = kvh * G + g
             q = batch.q[i, hq].float().cpu().numpy()
             ref = oa.attention_single(q, K, V, 1.0 / math.sqrt(D))
-            got = batch.out[i, hq].double().cpu().numpy()
-            worst = max(worst, float(np.abs(got - ref).max()))
-    assert worst <= tol, f"max-abs err {worst:.3e}"
+            for name, out in outs.items():
+                got = out[i, hq].double().cpu().numpy()
+                err = pbnd.assert_parity(got, ref, "bf16", name, mc,
+                                         what=f"request {req} ({K.shape[0]} tokens) head {hq} out {name}")
+                if name == "fp32":
+                    worst = max(worst, err)
     return worst
+
+
+def _run_both(lib, pool, batch):
+    """fp32 output (tight bound) and the benchmark's bf16 output."""
+    import torch
+    out16 = batch.out
+    out32 = torch.empty(batch.q.shape, dtype=torch.float32, device=batch.q.device)
+    batch.out = out32
+    _run(lib, pool, batch)
+    batch.out = out16
+    _run(lib, pool, batch)
+    return {"fp32": out32, "bf16": out16}
 
 
 def test_full_size_mha_workload_sampled(lib):
     """configs[2]: aligned batches 0 (longest, 32768-token requests), 7 and 15
-    (shortest) and random batch 3; bf16 out as in the benchmark; 1.5e-2."""
+    (shortest) and random batch 3; fp32 out at 1e-5 and bf16 out as in the
+    benchmark."""
     lens = wl.config_lengths(2)
     pool = harness.make_device_pool(lens, 32, 32, 128, dtype="bf16", seed=0)
     order, offs = lib.aligned_batch(lens, 64)
@@ -52,15 +75,16 @@ def test_full_size_mha_workload_sampled(lib):
     r_batches = harness.make_device_batches(pool, r_order, r_offs, seed=0)
     rng = np.random.default_rng(0)
     for b in (batches[0], batches[7], batches[15], r_batches[3]):
-        _run(lib, pool, b)
+        outs = _run_both(lib, pool, b)
         picks = [(int(i), int(h)) for i, h in zip(rng.integers(0, 64, 5), rng.integers(0, 32, 5))]
         picks += [(0, 0), (63, 31), (int(np.argmax(b.kv_lens_host)), 7), (int(np.argmin(b.kv_lens_host)), 19)]
-        _check_samples(pool, b, picks, 1.5e-2, G=1)
+        _check_samples(pool, b, picks, 1, outs)
+    assert int(batches[0].kv_lens_host.max()) == 32768   # the longest requests were among the samples
 
 
 def test_full_size_gqa_long_context_sampled(lib):
     """configs[3]: batch 128, 64 q / 8 kv heads, D 128, U{4096..32768}: the
-    matrix-core kernel with split-KV at full size; fp32 out; 1.5e-2."""
+    matrix-core kernel with split-KV at full size; fp32 out at 1e-4."""
     import torch
     lens = wl.config_lengths(3)
     pool = harness.make_device_pool(lens, 64, 8, 128, dtype="bf16", seed=3)
@@ -70,7 +94,7 @@ def test_full_size_gqa_long_context_sampled(lib):
     rng = np.random.default_rng(1)
     picks = [(int(i), int(h)) for i, h in zip(rng.integers(0, 128, 4), rng.integers(0, 8, 4))]
     picks += [(int(np.argmax(lens)), 0), (int(np.argmin(lens)), 7)]
-    _check_samples(pool, b, picks, 1.5e-2, G=8)
+    _check_samples(pool, b, picks, 8, {"fp32": b.out})
 
 
 def test_full_size_7b_ragged_batch_whole(lib):
@@ -79,6 +103,6 @@ def test_full_size_7b_ragged_batch_whole(lib):
     lens = wl.config_lengths(1)
     pool = harness.make_device_pool(lens, 32, 32, 128, dtype="bf16", seed=11)
     b = harness.make_device_batches(pool, np.arange(64), np.array([0, 64]), seed=7)[0]
-    _run(lib, pool, b)
+    outs = _run_both(lib, pool, b)
     picks = [(i, h) for i in (0, 13, 27, 40, 55, 63) for h in range(32)]
-    _check_samples(pool, b, picks, 1.5e-2, G=1)
+    _check_samples(pool, b, picks, 1, outs)
