@@ -203,6 +203,38 @@ as_status as_decode_attention(const void* q, const void* k_blocks, const void* v
                               size_t workspace_bytes, void* hip_stream);
 
 /* --------------------------------------------------------------------------
+ * as_decode_attention for callers that cannot allocate device memory or
+ * bring a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * result as as_decode_attention, minus the workspace: the work plan and the
+ * split-KV partials go to a static device array of AS_STATIC_SCRATCH_BYTES
+ * that is part of the library's code object (every GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates and frees
+ * nothing, on the host or on the device.
+ *   - A call whose plan and partials need more than the array (the figure
+ *     as_decode_attention_workspace gives for the same parameters and
+ *     total) is rejected with AS_EWORKSPACE before anything is enqueued;
+ *     32 MiB holds e.g. 128 requests x 64 query heads x 8 chunks.
+ *   - All calls on one GPU share that GPU's array, which keeps the previous
+ *     call's contents.  Nothing in it has to start at zero: a call reads only
+ *     what it has written itself (with AS_ATTN_REUSE_PLAN: what the previous
+ *     static call on this GPU, made with the same lengths and shape, wrote).
+ *     Calls that overlap on one GPU -- two streams, two threads, or a captured
+ *     graph replayed next to an eager call -- race on it: order them on one
+ *     stream or with events.
+ *   - The array's address is looked up on the first call on each device
+ *     (with that device current); later calls only read it.
+ * as_decode_attention_static_capacity returns AS_STATIC_SCRATCH_BYTES.
+ * Errors: those of as_decode_attention.
+ * -------------------------------------------------------------------------- */
+#define AS_STATIC_SCRATCH_BYTES (32u << 20)
+size_t as_decode_attention_static_capacity(void);
+as_status as_decode_attention_static(const void* q, const void* k_blocks, const void* v_blocks,
+                                     const int32_t* block_table, const int32_t* kv_lens,
+                                     const int32_t* kv_lens_host, void* out,
+                                     const as_attn_params* p, void* hip_stream);
+
+/* --------------------------------------------------------------------------
  * KV append (paper Section 2.1: a generated token's key and value join the
  * request's KVCache and take part in every later iteration).
  * For every request b of the batch, writes k_new[b] and v_new[b]

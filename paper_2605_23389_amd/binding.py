@@ -32,6 +32,7 @@ EXPORTS = [
     "as_qtree_next_batch", "as_dfs_batches", "as_kv_append", "as_sched_create", "as_sched_destroy",
     "as_sched_push_candidate_batch", "as_sched_push_candidate_request", "as_sched_step",
     "as_sched_state", "as_sched_running", "as_stage_set_policy",
+    "as_decode_attention_static", "as_decode_attention_static_capacity",
 ]
 
 
@@ -77,6 +78,10 @@ def load() -> C.CDLL:
     lib.as_decode_attention.restype = C.c_int
     lib.as_decode_attention.argtypes = [vp, vp, vp, vp, vp, i32p, vp, C.POINTER(AttnParams), vp,
                                         C.c_size_t, vp]
+    lib.as_decode_attention_static.restype = C.c_int
+    lib.as_decode_attention_static.argtypes = [vp, vp, vp, vp, vp, i32p, vp, C.POINTER(AttnParams), vp]
+    lib.as_decode_attention_static_capacity.restype = C.c_size_t
+    lib.as_decode_attention_static_capacity.argtypes = []
     lib.as_kv_read_sweep.restype = C.c_int
     lib.as_kv_read_sweep.argtypes = [vp, vp, vp, vp, i32p, vp, C.POINTER(AttnParams), vp,
                                      C.c_size_t, vp]
@@ -244,6 +249,25 @@ def decode_attention(q, k_blocks, v_blocks, block_table, kv_lens, out, kv_lens_h
                                    block_table.data_ptr(), kv_lens.data_ptr(),
                                    _ptr(host, C.c_int32), out.data_ptr(), C.byref(params),
                                    workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+    return out
+
+
+def decode_attention_static_capacity() -> int:
+    return int(load().as_decode_attention_static_capacity())
+
+
+def decode_attention_static(q, k_blocks, v_blocks, block_table, kv_lens, out, kv_lens_host=None,
+                            scale: float = 0.0, chunk_tokens: int = 0, flags: int = 0, stream=None,
+                            params: Optional[AttnParams] = None):
+    """decode_attention without a workspace: plan and partials go to the
+    library's static device array (no allocation anywhere).  Returns `out`."""
+    if params is None:
+        params = attn_params(q, k_blocks, block_table, out, scale, chunk_tokens, flags)
+    host = None if kv_lens_host is None else _i32(kv_lens_host)
+    _check(load().as_decode_attention_static(q.data_ptr(), k_blocks.data_ptr(), v_blocks.data_ptr(),
+                                             block_table.data_ptr(), kv_lens.data_ptr(),
+                                             _ptr(host, C.c_int32), out.data_ptr(), C.byref(params),
+                                             _stream_ptr(stream)))
     return out
 
 

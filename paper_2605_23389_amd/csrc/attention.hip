@@ -34,6 +34,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 
 #include "common.h"
 
@@ -1274,8 +1275,18 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
       }
     }
     out->icu.first[p->batch] = static_cast<uint16_t>(n);
-    std::stable_sort(last, last + nlast, [](const Last& x, const Last& y) { return x.tokens > y.tokens; });
-    for (int i = 0; i < nlast; ++i) out->ip.item[pos++] = last[i].word;
+    // last chunks from long to short, equal lengths in request order: a
+    // counting sort over the 1..chunk tokens a last chunk can hold (on the
+    // stack: this path allocates nothing)
+    uint16_t start[kMaxChunk + 2] = {};
+    for (int i = 0; i < nlast; ++i) ++start[last[i].tokens];
+    uint32_t run = pos;
+    for (int t = out->chunk; t >= 1; --t) {
+      const uint16_t c = start[t];
+      start[t] = static_cast<uint16_t>(run);
+      run += c;
+    }
+    for (int i = 0; i < nlast; ++i) out->ip.item[start[last[i].tokens]++] = last[i].word;
     out->use_inline = true;
   }
   if (out->items * p->num_q_heads > 0x7FFFFFFFLL)
@@ -1359,21 +1370,25 @@ extern "C" size_t as_decode_attention_workspace(const as_attn_params* p, int64_t
   return layout_for(*p, total_kv_tokens / chunk + p->batch).total;
 }
 
-extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, const void* v_blocks,
-                                         const int32_t* block_table, const int32_t* kv_lens,
-                                         const int32_t* kv_lens_host, void* out,
-                                         const as_attn_params* p, void* workspace,
-                                         size_t workspace_bytes, void* hip_stream) {
+namespace {
+
+// Shared body of as_decode_attention and as_decode_attention_static: argument
+// checks, then the plan / attention / combine launches on `ws`.
+as_status run_decode_attention(const char* what, const void* q, const void* k_blocks,
+                               const void* v_blocks, const int32_t* block_table,
+                               const int32_t* kv_lens, const int32_t* kv_lens_host, void* out,
+                               const as_attn_params* p, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
   if (!q || !k_blocks || !v_blocks || !block_table || !kv_lens || !out || !workspace)
-    return als::fail(AS_EINVAL, "as_decode_attention: a required pointer is null");
+    return als::fail(AS_EINVAL, "%s: a required pointer is null", what);
   // the kernels move q, K, V and the result with 128-bit accesses
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_blocks) |
        reinterpret_cast<uintptr_t>(v_blocks) | reinterpret_cast<uintptr_t>(out)) % 16)
-    return als::fail(AS_EINVAL, "as_decode_attention: q, k_blocks, v_blocks and out must be 16-byte aligned");
+    return als::fail(AS_EINVAL, "%s: q, k_blocks, v_blocks and out must be 16-byte aligned", what);
   if ((reinterpret_cast<uintptr_t>(block_table) | reinterpret_cast<uintptr_t>(kv_lens)) % 4)
-    return als::fail(AS_EINVAL, "as_decode_attention: block_table and kv_lens must be 4-byte aligned");
+    return als::fail(AS_EINVAL, "%s: block_table and kv_lens must be 4-byte aligned", what);
   Checked ck;
-  as_status st = validate("as_decode_attention", p, kv_lens_host, workspace_bytes, workspace, &ck);
+  as_status st = validate(what, p, kv_lens_host, workspace_bytes, workspace, &ck);
   if (st != AS_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
@@ -1429,6 +1444,67 @@ extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, co
     ALS_HIP_CHECK(hipGetLastError());
   }
   return AS_OK;
+}
+
+}  // namespace
+
+extern "C" as_status as_decode_attention(const void* q, const void* k_blocks, const void* v_blocks,
+                                         const int32_t* block_table, const int32_t* kv_lens,
+                                         const int32_t* kv_lens_host, void* out,
+                                         const as_attn_params* p, void* workspace,
+                                         size_t workspace_bytes, void* hip_stream) {
+  return run_decode_attention("as_decode_attention", q, k_blocks, v_blocks, block_table, kv_lens,
+                              kv_lens_host, out, p, workspace, workspace_bytes, hip_stream);
+}
+
+// ------------------------------------------------------------------ static scratch
+// The variant for callers that cannot allocate: the plan and the split-KV
+// partials live in one file-scope device array instead of a caller workspace.
+// `scratch` names the array for the compiler only -- in host code it is a
+// stand-in, not a device address; the address on each device comes from
+// hipGetSymbolAddress, once per device, and that pointer is what the kernels
+// get.
+static __device__ __align__(256) unsigned char scratch[AS_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // per device: each GPU holds its own copy of the array
+
+as_status static_scratch(void** out) {
+  int dev = -1;
+  ALS_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices)
+    return als::fail(AS_EUNSUPPORTED, "as_decode_attention_static: device index %d is beyond %d", dev,
+                     kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    ALS_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 256)
+      return als::fail(AS_EHIP, "as_decode_attention_static: bad address %p for the scratch array", ptr);
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return AS_OK;
+}
+
+}  // namespace
+
+extern "C" size_t as_decode_attention_static_capacity(void) { return AS_STATIC_SCRATCH_BYTES; }
+
+extern "C" as_status as_decode_attention_static(const void* q, const void* k_blocks,
+                                                const void* v_blocks, const int32_t* block_table,
+                                                const int32_t* kv_lens, const int32_t* kv_lens_host,
+                                                void* out, const as_attn_params* p, void* hip_stream) {
+  void* ws = nullptr;
+  const as_status st = static_scratch(&ws);
+  if (st != AS_OK) return st;
+  // validate() turns a plan + partials larger than the array into AS_EWORKSPACE
+  // before anything is enqueued
+  return run_decode_attention("as_decode_attention_static", q, k_blocks, v_blocks, block_table, kv_lens,
+                              kv_lens_host, out, p, ws, AS_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks,
