@@ -269,6 +269,39 @@ def paper_shaped_leg(args, torch, als, harness, traffic, wl, log):
     return out
 
 
+def decode_loop_leg(args, torch, als, wl, log, Hq, Hkv, D, n_sim=384):
+    """Multi-iteration decode loop (Algorithm 2 every iteration, KV append + attention per
+    iteration) on a block pool tight enough for evictions, for {prefix-aware, arrival-order}
+    candidate batches x {candidate-buffer prefetch on, off}.  One layer's KV per token."""
+    from paper_2605_23389_amd import decode_sim
+    rng = np.random.default_rng(args.seed + 5)
+    prefix = wl.lognormal_lengths(rng, n_sim, 1024.0, 1.2, 64, 16384)
+    outs = rng.integers(96, 289, n_sim).astype(np.int32)
+    loop = {}
+    for policy in ("aligned", "fcfs"):
+        for prefetch in (True, False):
+            cfg = decode_sim.SimConfig(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, max_batch=64,
+                                       hbm_blocks=6144, policy=policy, host_arena_blocks=4096,
+                                       evict_slots=16, seed=args.seed, prefetch=prefetch)
+            sim = decode_sim.DecodeSim(prefix, outs, cfg)
+            key = f"{policy}_prefetch_{'on' if prefetch else 'off'}"
+            loop[key] = decode_sim.summarize(sim.run())
+            r = loop[key]
+            log(f"decode loop {key}: {r['iterations']} it, attn p50/p99 {r['attn_us_p50']}/{r['attn_us_p99']} us, "
+                f"gap p50/p90/p99 {r['schedule_gap_us_p50']}/{r['schedule_gap_us_p90']}/{r['schedule_gap_us_p99']} us, "
+                f"{r['tokens_per_s']:.0f} tok/s, evictions {r['evictions']}")
+            del sim
+            torch.cuda.empty_cache()
+    loop["note"] = (f"{n_sim} requests, prefix lognormal(1024, s1.2) clip [64,16384], 96-288 output tokens, 7B-shaped "
+                    "layer (one layer's KV per token), running batch <= 64 under a 6144-block HBM budget (768 MiB per "
+                    "pool: block-limited, so Algorithm 2 evicts), candidate buffers = a second budget of the same "
+                    "pool; candidate batches from the quad-tree generator (K_min 36, B_max 40 %) vs arrival order; "
+                    "schedule gap = end of an iteration's attention to the start of the next iteration's work on "
+                    "the compute stream (host scheduling in Python + any wait for staging copies); prefetch off = "
+                    "a request is staged when Algorithm 2 admits it; tokens_per_s counts gaps and iterations")
+    return loop
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -284,6 +317,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--only-pipeline", action="store_true",
                     help="profiling aid: run only the scaled configs[4] staging/attention pipeline and print its line")
+    ap.add_argument("--only-decode-loop", action="store_true",
+                    help="run only the multi-iteration decode loop leg and print its line")
     ap.add_argument("--only-cfg3", action="store_true",
                     help="profiling aid: run only the GQA long-context batch (configs[3]) and print its line")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -306,6 +341,12 @@ def main():
     if args.only_pipeline:
         print(json.dumps({"workload": "configs[4] host-resident KV pipeline (scaled)",
                           **pipeline_leg(args, torch, als, harness, traffic, wl, log)}), flush=True)
+        return
+    if args.only_decode_loop:
+        sh = wl.CONFIG_SHAPES[2]
+        print(json.dumps({"workload": "multi-iteration decode loop",
+                          **decode_loop_leg(args, torch, als, wl, log, sh["num_q_heads"], sh["num_kv_heads"],
+                                            sh["head_dim"])}), flush=True)
         return
     if args.only_cfg3:
         if args.copy_calibration:
@@ -663,29 +704,11 @@ def main():
         log(f"cfg3: {rows3}")
         del pool3, b3
 
-        # ---------------- multi-iteration decode loop: prefix-aware vs FCFS candidate batches
+        # ---------------- multi-iteration decode loop: prefix-aware vs FCFS candidate batches,
+        # candidate-buffer prefetch on vs off (the one-GPU analogue of the paper's time-to-schedule
+        # CDF, Fig. 10, and of its GPU-prefetch ablation, Fig. 13)
         try:
-            from paper_2605_23389_amd import decode_sim
-            rng = np.random.default_rng(args.seed + 5)
-            n_sim = 512
-            prefix = wl.lognormal_lengths(rng, n_sim, 1024.0, 1.2, 64, 16384)
-            outs = rng.integers(16, 65, n_sim).astype(np.int32)
-            loop = {}
-            for policy in ("aligned", "fcfs"):
-                cfg = decode_sim.SimConfig(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, max_batch=64,
-                                           hbm_blocks=32768, policy=policy, host_arena_blocks=4096,
-                                           evict_slots=8, seed=args.seed)
-                sim = decode_sim.DecodeSim(prefix, outs, cfg)
-                loop[policy] = decode_sim.summarize(sim.run())
-                del sim
-                torch.cuda.empty_cache()
-            loop["note"] = ("512 requests, prefix lognormal(1024, s1.2) clip [64,16384], 16-64 output tokens, "
-                            "7B-shaped layer, running batch <= 64, 32768 HBM blocks; candidate batches from the "
-                            "quad-tree generator (K_min 36, B_max 40 %) vs arrival order; Algorithm 2 schedules "
-                            "every iteration; times are the attention launch of each iteration")
-            result["decode_loop"] = loop
-            log(f"decode loop: aligned p50/p99 {loop['aligned']['attn_us_p50']}/{loop['aligned']['attn_us_p99']} us, "
-                f"fcfs {loop['fcfs']['attn_us_p50']}/{loop['fcfs']['attn_us_p99']} us")
+            result["decode_loop"] = decode_loop_leg(args, torch, als, wl, log, Hq, Hkv, D)
         except Exception as e:
             result["decode_loop"] = {"error": repr(e)}
             log(f"decode loop leg failed: {e!r}")

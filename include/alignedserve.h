@@ -354,6 +354,10 @@ as_status as_unstage_kv(void* host_k, void* host_v, const int64_t* dst_ids,
  *   as_pipeline_end_stage(buf)      records buf's "ready" on the side stream
  *   as_pipeline_acquire(buf, s)     stream s waits for buf's "ready"
  *   as_pipeline_release(buf, s)     records buf's "free" on stream s
+ *   as_pipeline_query(buf, &ready)  host-side poll, no wait: *ready = 1 when
+ *                        the copies last closed by end_stage(buf) have
+ *                        finished (or none were ever staged), else 0; lets a
+ *                        scheduler admit only what is already resident
  *   as_pipeline_destroy  synchronises the side stream, destroys everything
  * Errors: AS_EINVAL (null pipeline, buf out of range), AS_EHIP.
  * -------------------------------------------------------------------------- */
@@ -364,6 +368,7 @@ as_status as_pipeline_begin_stage(as_pipeline* p, int32_t buf);
 as_status as_pipeline_end_stage(as_pipeline* p, int32_t buf);
 as_status as_pipeline_acquire(as_pipeline* p, int32_t buf, void* hip_stream);
 as_status as_pipeline_release(as_pipeline* p, int32_t buf, void* hip_stream);
+as_status as_pipeline_query(as_pipeline* p, int32_t buf, int32_t* ready);
 as_status as_pipeline_destroy(as_pipeline* p);
 
 /* --------------------------------------------------------------------------

@@ -32,7 +32,7 @@ EXPORTS = [
     "as_qtree_next_batch", "as_dfs_batches", "as_kv_append", "as_sched_create", "as_sched_destroy",
     "as_sched_push_candidate_batch", "as_sched_push_candidate_request", "as_sched_step",
     "as_sched_state", "as_sched_running", "as_stage_set_policy",
-    "as_decode_attention_static", "as_decode_attention_static_capacity",
+    "as_decode_attention_static", "as_decode_attention_static_capacity", "as_pipeline_query",
 ]
 
 
@@ -103,6 +103,8 @@ def load() -> C.CDLL:
     for name in ("as_pipeline_acquire", "as_pipeline_release"):
         getattr(lib, name).restype = C.c_int
         getattr(lib, name).argtypes = [vp, C.c_int32, vp]
+    lib.as_pipeline_query.restype = C.c_int
+    lib.as_pipeline_query.argtypes = [vp, C.c_int32, i32p]
     lib.as_pipeline_destroy.restype = C.c_int
     lib.as_pipeline_destroy.argtypes = [vp]
     lib.as_kv_append.restype = C.c_int
@@ -240,6 +242,11 @@ def decode_attention(q, k_blocks, v_blocks, block_table, kv_lens, out, kv_lens_h
         if host.shape[0] != q.shape[0]:
             raise AlignedServeError(AS_EINVAL, "kv_lens_host has the wrong length")
     if workspace is None:
+        # The temporary below belongs to torch's caching allocator on the CURRENT stream and is
+        # released when this call returns; that is safe only for work enqueued on that same stream.
+        if _stream_ptr(stream) != torch.cuda.current_stream().cuda_stream:
+            raise AlignedServeError(AS_EINVAL, "pass a workspace when launching on a stream other than "
+                                               "torch's current stream")
         total = int(host.sum()) if host is not None else -1
         nbytes = decode_attention_workspace(params, total)
         if nbytes == 0:
@@ -334,6 +341,12 @@ class Pipeline:
 
     def release(self, buf: int, stream=None):
         _check(load().as_pipeline_release(self._h, buf, _stream_ptr(stream)))
+
+    def query(self, buf: int) -> bool:
+        """True when the copies last closed by end_stage(buf) have finished."""
+        r = C.c_int32(0)
+        _check(load().as_pipeline_query(self._h, buf, C.byref(r)))
+        return bool(r.value)
 
     def destroy(self):
         if self._h:

@@ -271,6 +271,16 @@ extern "C" as_status as_pipeline_acquire(as_pipeline* p, int32_t buf, void* hip_
   return AS_OK;
 }
 
+extern "C" as_status as_pipeline_query(as_pipeline* p, int32_t buf, int32_t* ready) {
+  ALS_PIPE_ARGS("as_pipeline_query");
+  if (!ready) return als::fail(AS_EINVAL, "as_pipeline_query: ready is null");
+  const hipError_t e = hipEventQuery(p->ready[buf]);  // a never-recorded event reads as complete
+  if (e != hipSuccess && e != hipErrorNotReady)
+    return als::fail(AS_EHIP, "as_pipeline_query: %s", hipGetErrorString(e));
+  *ready = e == hipSuccess ? 1 : 0;
+  return AS_OK;
+}
+
 extern "C" as_status as_pipeline_release(as_pipeline* p, int32_t buf, void* hip_stream) {
   ALS_PIPE_ARGS("as_pipeline_release");
   ALS_HIP_CHECK(hipEventRecord(p->free_[buf], static_cast<hipStream_t>(hip_stream)));
