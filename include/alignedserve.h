@@ -9,9 +9,10 @@
  *     the caller, "host" pointers are ordinary host memory unless stated to
  *     be pinned;
  *   - the library never allocates or frees caller-visible memory;
- *   - every call returns an as_status and never throws; on failure nothing
- *     has been enqueued unless the status is AS_EHIP, and as_last_error()
- *     returns a thread-local, library-owned description;
+ *   - every call returns an as_status and never throws (a C++ exception
+ *     raised inside, such as std::bad_alloc, comes back as AS_ENOMEM); on
+ *     failure nothing has been enqueued unless the status is AS_EHIP, and
+ *     as_last_error() returns a thread-local, library-owned description;
  *   - calls that take a stream are asynchronous on it and return after
  *     enqueueing; a null stream is the HIP default stream.
  *
@@ -41,7 +42,9 @@ typedef enum {
   AS_ERANGE = 2,       /* a value outside what the arguments allow              */
   AS_EWORKSPACE = 3,   /* workspace smaller than as_decode_attention_workspace  */
   AS_EUNSUPPORTED = 4, /* dtype / head_dim / block_size the kernels do not have */
-  AS_EHIP = 5          /* a HIP runtime call failed (message has its string)    */
+  AS_EHIP = 5,         /* a HIP runtime call failed (message has its string)    */
+  AS_ENOMEM = 6        /* host memory ran out inside the library; the object the
+                          call was to change is as it was before the call        */
 } as_status;
 
 #define AS_DTYPE_F32 0

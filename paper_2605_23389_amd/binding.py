@@ -16,9 +16,9 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libalignedserve.so")
 
-AS_OK, AS_EINVAL, AS_ERANGE, AS_EWORKSPACE, AS_EUNSUPPORTED, AS_EHIP = range(6)
+AS_OK, AS_EINVAL, AS_ERANGE, AS_EWORKSPACE, AS_EUNSUPPORTED, AS_EHIP, AS_ENOMEM = range(7)
 STATUS_NAMES = {0: "AS_OK", 1: "AS_EINVAL", 2: "AS_ERANGE", 3: "AS_EWORKSPACE",
-                4: "AS_EUNSUPPORTED", 5: "AS_EHIP"}
+                4: "AS_EUNSUPPORTED", 5: "AS_EHIP", 6: "AS_ENOMEM"}
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 ATTN_REUSE_PLAN, ATTN_NO_MFMA = 1, 2
 STAGE_AUTO, STAGE_DMA, STAGE_KERNEL = 0, 1, 2

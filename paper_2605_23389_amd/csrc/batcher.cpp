@@ -44,6 +44,7 @@ extern "C" as_status as_aligned_batch(const int32_t* kv_lens, int32_t n, int32_t
                        kv_lens[i]);
 
   const int64_t nb = (static_cast<int64_t>(n) + batch_size - 1) / batch_size;
+  ALS_TRY
   if (n > 0) {
     // key = bitwise complement of the (positive) length: ascending key <=> descending length
     std::vector<uint32_t> key_a(n), key_b(n);
@@ -77,6 +78,7 @@ extern "C" as_status as_aligned_batch(const int32_t* kv_lens, int32_t n, int32_t
     }
     if (ia != order) std::memcpy(order, ia, sizeof(int32_t) * static_cast<size_t>(n));
   }
+  ALS_CATCH("as_aligned_batch")
   for (int64_t j = 0; j <= nb; ++j) {
     const int64_t off = j * batch_size;
     batch_offsets[j] = static_cast<int32_t>(off < n ? off : n);

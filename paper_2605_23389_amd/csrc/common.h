@@ -4,6 +4,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <new>
 
 #include "alignedserve.h"
 
@@ -20,6 +21,19 @@ inline as_status fail(as_status st, const char* fmt, ...) {
 }
 
 }  // namespace als
+
+// No C++ exception may cross the C ABI: entry points that allocate run their
+// body between these two.  The bodies are written so that everything that can
+// throw happens before the first change to the object they work on.
+#define ALS_TRY try {
+#define ALS_CATCH(name)                                                              \
+  }                                                                                  \
+  catch (const std::bad_alloc&) {                                                    \
+    return als::fail(AS_ENOMEM, name ": out of host memory");                        \
+  }                                                                                  \
+  catch (...) {                                                                      \
+    return als::fail(AS_ENOMEM, name ": unexpected C++ exception");                  \
+  }
 
 #define ALS_HIP_CHECK(expr)                                                          \
   do {                                                                               \

@@ -19,6 +19,7 @@
 // lines.  Leaves keep their requests sorted by (length, id).
 #include <algorithm>
 #include <cstdint>
+#include <memory>
 #include <unordered_map>
 #include <vector>
 
@@ -80,7 +81,8 @@ extern "C" as_status as_qtree_create(as_qtree** out, int32_t max_len, int32_t le
   }
   if (span != leaf_width || levels > 12)
     return als::fail(AS_EINVAL, "as_qtree_create: max_len / leaf_width must be a power of four (at most 4^12)");
-  as_qtree* t = new as_qtree();
+  ALS_TRY
+  std::unique_ptr<as_qtree> t(new as_qtree());
   t->max_len = max_len;
   t->leaf_width = leaf_width;
   t->levels = levels;
@@ -92,7 +94,8 @@ extern "C" as_status as_qtree_create(as_qtree** out, int32_t max_len, int32_t le
     t->stamp.emplace_back(n, 0.0);
   }
   t->leaves.resize(size_t{1} << (2 * levels));
-  *out = t;
+  *out = t.release();
+  ALS_CATCH("as_qtree_create")
   return AS_OK;
 }
 
@@ -110,15 +113,23 @@ extern "C" as_status as_qtree_insert(as_qtree* t, int32_t request_id, int32_t pr
   if (t->by_id.count(request_id))
     return als::fail(AS_EINVAL, "as_qtree_insert: request %d is already in the tree", request_id);
   const Req r{std::min(prefix_len, t->max_len), request_id, blocks};
+  // the two steps that allocate come first; the counters change only once both have succeeded
+  ALS_TRY
+  t->by_id.emplace(request_id, r);
+  try {
+    auto& leaf = t->leaves[t->node_of(t->levels, r.len)];
+    leaf.insert(std::lower_bound(leaf.begin(), leaf.end(), r), r);
+  } catch (...) {
+    t->by_id.erase(request_id);
+    throw;
+  }
+  ALS_CATCH("as_qtree_insert")
   for (int l = 0; l <= t->levels; ++l) {
     const int64_t i = t->node_of(l, r.len);
     if (t->req_count[l][i] == 0) t->stamp[l][i] = now;  // age counts from the first arrival
     t->req_count[l][i] += 1;
     t->blk_count[l][i] += blocks;
   }
-  auto& leaf = t->leaves[t->node_of(t->levels, r.len)];
-  leaf.insert(std::lower_bound(leaf.begin(), leaf.end(), r), r);
-  t->by_id.emplace(request_id, r);
   return AS_OK;
 }
 
@@ -167,8 +178,10 @@ extern "C" as_status as_qtree_next_batch(as_qtree* t, int64_t b_max, int32_t k_m
     }
   }
 
+  // the batch is gathered into local storage (the only part that allocates); the tree changes after it
   std::vector<Req> batch;
   int which = 0;
+  ALS_TRY
   for (;;) {
     const int64_t used = t->blk_count[level][idx];
     const int64_t count = t->req_count[level][idx];
@@ -229,6 +242,7 @@ extern "C" as_status as_qtree_next_batch(as_qtree* t, int64_t b_max, int32_t k_m
     which = 3;
     break;
   }
+  ALS_CATCH("as_qtree_next_batch")
 
   if (static_cast<int64_t>(batch.size()) > capacity)
     return als::fail(AS_ERANGE, "as_qtree_next_batch: batch of %zu requests exceeds capacity %d", batch.size(), capacity);

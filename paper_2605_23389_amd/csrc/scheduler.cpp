@@ -13,8 +13,9 @@
 // admission takes requests in buffer order while the batch is below
 // max_batch and the request's blocks plus next-iteration growth fit, and
 // stops at the first that does not.
+#include <algorithm>
 #include <cstdint>
-#include <deque>
+#include <memory>
 #include <vector>
 
 #include "common.h"
@@ -23,13 +24,37 @@ namespace {
 struct SReq {
   int32_t id, kv_len, remaining, origin;
 };
+
+// First-in first-out buffer over one vector.  Unlike std::deque it can reserve
+// room ahead of time, so that a scheduling pass does all its allocation before
+// it changes anything and cannot fail half way.
+struct Fifo {
+  std::vector<SReq> v;
+  size_t head = 0;
+  bool empty() const { return head == v.size(); }
+  size_t size() const { return v.size() - head; }
+  const SReq& front() const { return v[head]; }
+  void pop_front() {
+    if (++head == v.size()) { v.clear(); head = 0; }
+  }
+  void push_back(const SReq& r) { v.push_back(r); }
+  void pop_back() { v.pop_back(); }
+  // room for `extra` more entries without a further allocation (may throw; changes no content)
+  void reserve_extra(size_t extra) {
+    if (head > 0 && v.size() + extra > v.capacity()) {
+      v.erase(v.begin(), v.begin() + static_cast<std::ptrdiff_t>(head));  // moves only, no allocation
+      head = 0;
+    }
+    v.reserve(v.size() + extra);
+  }
+};
 }  // namespace
 
 struct as_sched {
   int64_t total, free_;
   int32_t bs, max_batch;
   std::vector<SReq> running;
-  std::deque<SReq> r_cand, b_cand;
+  Fifo r_cand, b_cand;
 
   int64_t blocks(const SReq& r) const { return (static_cast<int64_t>(r.kv_len) + bs - 1) / bs; }
   int64_t growth() const {
@@ -44,11 +69,14 @@ extern "C" as_status as_sched_create(as_sched** out, int64_t total_blocks, int32
   if (!out) return als::fail(AS_EINVAL, "as_sched_create: out is null");
   if (total_blocks < 1 || block_size < 1 || max_batch < 1)
     return als::fail(AS_EINVAL, "as_sched_create: total_blocks, block_size and max_batch must be positive");
-  as_sched* s = new as_sched();
+  ALS_TRY
+  std::unique_ptr<as_sched> s(new as_sched());
   s->total = s->free_ = total_blocks;
   s->bs = block_size;
   s->max_batch = max_batch;
-  *out = s;
+  s->running.reserve(static_cast<size_t>(max_batch));
+  *out = s.release();
+  ALS_CATCH("as_sched_create")
   return AS_OK;
 }
 
@@ -67,6 +95,9 @@ extern "C" as_status as_sched_push_candidate_batch(as_sched* s, int32_t origin, 
     if (kv_lens[i] < 1 || remaining[i] < 1)
       return als::fail(AS_EINVAL, "as_sched_push_candidate_batch: request %d has kv_len %d, remaining %d", ids[i],
                        kv_lens[i], remaining[i]);
+  ALS_TRY
+  s->b_cand.reserve_extra(static_cast<size_t>(n));   // all or nothing
+  ALS_CATCH("as_sched_push_candidate_batch")
   for (int32_t i = 0; i < n; ++i) s->b_cand.push_back(SReq{ids[i], kv_lens[i], remaining[i], origin});
   return AS_OK;
 }
@@ -76,6 +107,9 @@ extern "C" as_status as_sched_push_candidate_request(as_sched* s, int32_t origin
   if (!s) return als::fail(AS_EINVAL, "as_sched_push_candidate_request: scheduler is null");
   if (kv_len < 1 || remaining < 1)
     return als::fail(AS_EINVAL, "as_sched_push_candidate_request: kv_len and remaining must be positive");
+  ALS_TRY
+  s->r_cand.reserve_extra(1);
+  ALS_CATCH("as_sched_push_candidate_request")
   s->r_cand.push_back(SReq{id, kv_len, remaining, origin});
   return AS_OK;
 }
@@ -88,6 +122,12 @@ extern "C" as_status as_sched_step(as_sched* s, int32_t advance, int32_t* comple
   // every list is bounded by the running batch before the step plus what can be admitted
   if (capacity < static_cast<int32_t>(s->running.size()) || capacity < s->max_batch)
     return als::fail(AS_ERANGE, "as_sched_step: capacity %d is below the running batch / max_batch", capacity);
+  // every victim of this pass fits the candidate-requests buffer and every admission fits the running
+  // batch without a further allocation: past this point nothing can fail
+  ALS_TRY
+  s->r_cand.reserve_extra(s->running.size());
+  s->running.reserve(std::max(s->running.size(), static_cast<size_t>(s->max_batch)));
+  ALS_CATCH("as_sched_step")
   if (advance) {
     for (SReq& r : s->running) {
       const int64_t before = s->blocks(r);
@@ -129,7 +169,7 @@ extern "C" as_status as_sched_step(as_sched* s, int32_t advance, int32_t* comple
       evicted[ne++] = victim.id;
     }
   } else {
-    std::deque<SReq>* src = nullptr;
+    Fifo* src = nullptr;
     if (!s->r_cand.empty()) { src = &s->r_cand; which = 1; }
     else if (!s->b_cand.empty()) { src = &s->b_cand; which = 2; }
     if (src) {

@@ -228,7 +228,8 @@ extern "C" as_status as_pipeline_create(as_pipeline** out, int32_t num_buffers) 
   if (!out) return als::fail(AS_EINVAL, "as_pipeline_create: out is null");
   if (num_buffers < 1 || num_buffers > 8)
     return als::fail(AS_EINVAL, "as_pipeline_create: num_buffers = %d outside [1, 8]", num_buffers);
-  as_pipeline* p = new as_pipeline();
+  as_pipeline* p = new (std::nothrow) as_pipeline();
+  if (!p) return als::fail(AS_ENOMEM, "as_pipeline_create: out of host memory");
   p->num_buffers = num_buffers;
   p->side = nullptr;
   for (int i = 0; i < 8; ++i) p->ready[i] = p->free_[i] = nullptr;

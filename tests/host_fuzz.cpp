@@ -5,10 +5,57 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <new>
 #include <random>
 #include <vector>
 
 #include "alignedserve.h"
+
+// Allocation-failure injection: while armed, the k-th allocation from now
+// throws std::bad_alloc.  Armed only around a single library call.
+static long g_fail_in = -1;
+void* operator new(std::size_t n) {
+  if (g_fail_in >= 0 && g_fail_in-- == 0) throw std::bad_alloc();
+  if (void* p = std::malloc(n ? n : 1)) return p;
+  throw std::bad_alloc();
+}
+void* operator new(std::size_t n, const std::nothrow_t&) noexcept {
+  if (g_fail_in >= 0 && g_fail_in-- == 0) return nullptr;
+  return std::malloc(n ? n : 1);
+}
+void operator delete(void* p) noexcept { std::free(p); }
+void operator delete(void* p, std::size_t) noexcept { std::free(p); }
+
+// Runs `call` with the k-th allocation failing, k = 0, 1, 2, ...: every outcome must be AS_OK or
+// AS_ENOMEM (no exception may escape), `unchanged` must hold after an AS_ENOMEM, and the first
+// AS_OK ends the sweep.  Returns the number of injected failures that surfaced as AS_ENOMEM.
+template <typename Call, typename Check>
+static int sweep_failures(Call call, Check unchanged, bool* ok) {
+  int seen = 0;
+  for (long k = 0; k < 100000; k += 1 + k / 8) {   // every early allocation, then a thinning sample of later ones
+    g_fail_in = k;
+    as_status st;
+    try {
+      st = call();
+    } catch (...) {
+      g_fail_in = -1;
+      std::fprintf(stderr, "an exception crossed the C ABI (allocation %ld)\n", k);
+      *ok = false;
+      return seen;
+    }
+    const bool fired = g_fail_in < 0;
+    g_fail_in = -1;
+    if (st == AS_OK) { *ok = true; return seen; }
+    if (st != AS_ENOMEM || !fired || !unchanged()) {
+      std::fprintf(stderr, "allocation %ld failing: status %d, fired %d: %s\n", k, int(st), int(fired), as_last_error());
+      *ok = false;
+      return seen;
+    }
+    ++seen;
+  }
+  *ok = false;
+  return seen;
+}
 
 #define REQUIRE(x) do { if (!(x)) { std::fprintf(stderr, "REQUIRE failed: %s (line %d): %s\n", #x, __LINE__, as_last_error()); return 1; } } while (0)
 
@@ -94,6 +141,79 @@ int main() {
       REQUIRE(as_sched_step(s, 0, c.data(), &nc, e.data(), &ne, a.data(), &na, 0, &which) == AS_ERANGE);
     }
     REQUIRE(as_sched_destroy(s) == AS_OK);
+  }
+  // --- allocation failures: AS_ENOMEM, the object unchanged, nothing thrown across the ABI
+  {
+    bool ok = false;
+    int enomem = 0;
+    auto always = [] { return true; };
+    // batch formation
+    std::vector<int32_t> lens(300), order(300), offs(40);
+    for (int i = 0; i < 300; ++i) lens[i] = 1 + (i * 7919) % 5000;
+    int32_t nbat = 0;
+    enomem += sweep_failures([&] { return as_aligned_batch(lens.data(), 300, 8, order.data(), offs.data(), &nbat); }, always, &ok);
+    REQUIRE(ok && nbat == 38);
+    // quad-tree: create, insert, search
+    as_qtree* t = nullptr;
+    enomem += sweep_failures([&] { return as_qtree_create(&t, 65536, 16); }, [&] { return t == nullptr; }, &ok);
+    REQUIRE(ok && t != nullptr);
+    for (int i = 0; i < 200; ++i) {
+      int64_t r0 = 0, b0 = 0;
+      REQUIRE(as_qtree_size(t, &r0, &b0) == AS_OK);
+      auto same = [&] { int64_t r = 0, b = 0; return as_qtree_size(t, &r, &b) == AS_OK && r == r0 && b == b0; };
+      const int L = 1 + (i * 104729) % 60000;
+      enomem += sweep_failures([&] { return as_qtree_insert(t, i, L, L / 16 + 1, 0.0); }, same, &ok);
+      REQUIRE(ok);
+      // a failed insert must not have left the id behind: the same id can still be removed exactly once
+      int64_t r1 = 0, b1 = 0;
+      REQUIRE(as_qtree_size(t, &r1, &b1) == AS_OK && r1 == r0 + 1 && b1 == b0 + L / 16 + 1);
+    }
+    std::vector<int32_t> ids(256);
+    for (int round = 0; round < 6; ++round) {
+      int64_t r0 = 0, b0 = 0;
+      REQUIRE(as_qtree_size(t, &r0, &b0) == AS_OK);
+      auto same = [&] { int64_t r = 0, b = 0; return as_qtree_size(t, &r, &b) == AS_OK && r == r0 && b == b0; };
+      int32_t got = 0, which = 0;
+      enomem += sweep_failures([&] { return as_qtree_next_batch(t, 20000, 36, 1.0, -1.0, ids.data(), 256, &got, &which); }, same, &ok);
+      REQUIRE(ok);
+      int64_t r1 = 0, b1 = 0;
+      REQUIRE(as_qtree_size(t, &r1, &b1) == AS_OK && r1 == r0 - got);
+    }
+    REQUIRE(as_qtree_destroy(t) == AS_OK);
+    std::vector<int32_t> blocks(300);
+    for (int i = 0; i < 300; ++i) blocks[i] = lens[i] / 16 + 1;
+    std::vector<int32_t> offs2(301);
+    enomem += sweep_failures([&] { return as_dfs_batches(lens.data(), blocks.data(), 300, 4000, 36, 65536, 16, order.data(), offs2.data(), &nbat); }, always, &ok);
+    REQUIRE(ok && offs2[nbat] == 300);
+    // scheduler: create, push, step
+    as_sched* sc = nullptr;
+    enomem += sweep_failures([&] { return as_sched_create(&sc, 300, 16, 8); }, [&] { return sc == nullptr; }, &ok);
+    REQUIRE(ok && sc != nullptr);
+    int32_t next = 0;
+    for (int it = 0; it < 120; ++it) {
+      int64_t f0 = 0; int32_t a0 = 0, rc0 = 0, bc0 = 0;
+      REQUIRE(as_sched_state(sc, &f0, &a0, &rc0, &bc0) == AS_OK);
+      auto same = [&] { int64_t f = 0; int32_t a = 0, rc = 0, bc = 0;
+                        return as_sched_state(sc, &f, &a, &rc, &bc) == AS_OK && f == f0 && a == a0 && rc == rc0 && bc == bc0; };
+      if (bc0 == 0) {
+        int32_t bid[5], bl[5], br[5];
+        for (int i = 0; i < 5; ++i) { bid[i] = next++; bl[i] = 1 + (next * 37) % 700; br[i] = 1 + next % 30; }
+        enomem += sweep_failures([&] { return as_sched_push_candidate_batch(sc, it, bid, bl, br, 5); }, same, &ok);
+        REQUIRE(ok);
+        REQUIRE(as_sched_state(sc, &f0, &a0, &rc0, &bc0) == AS_OK && bc0 == 5);
+      }
+      if (it % 17 == 3) {
+        enomem += sweep_failures([&] { return as_sched_push_candidate_request(sc, it, next++, 40, 5); }, same, &ok);
+        REQUIRE(ok);
+        REQUIRE(as_sched_state(sc, &f0, &a0, &rc0, &bc0) == AS_OK);
+      }
+      int32_t c[64], e[64], a[64], nc = 0, ne = 0, na = 0, which = 0;
+      enomem += sweep_failures([&] { return as_sched_step(sc, it > 0, c, &nc, e, &ne, a, &na, 64, &which); }, same, &ok);
+      REQUIRE(ok);
+    }
+    REQUIRE(as_sched_destroy(sc) == AS_OK);
+    REQUIRE(enomem > 50);   // the injection really reached the library's allocations
+    std::printf("allocation failures surfaced as AS_ENOMEM: %d\n", enomem);
   }
   std::puts("host fuzz ok");
   return 0;
