@@ -1,7 +1,8 @@
 """Oracle for the paper's own batch generator: quad-tree + Density First Search.
 
-TEST INFRASTRUCTURE ONLY: plain Python objects and recursion, counters
-recomputed from scratch on every query; shares no code with the C++ library.
+TEST INFRASTRUCTURE ONLY: one flat table of requests and range queries over
+it; every counter is recomputed from the table on every query; shares no code
+with the C++ library.
 
 Paper Section 3.3.  In-flight requests live in the leaves of a quad-tree keyed
 on prefix length.  Every internal node covers a range of prefix lengths that
@@ -30,7 +31,8 @@ Readings where the paper is silent (listed in the design notes):
   * equal request counters: the leftmost child wins;
   * case 2 at a leaf (no children to descend into): requests are taken in
     ascending order while they fit B_max, and at least one is taken;
-  * case 3 follows the listing literally: one side only (left if present);
+  * case 3 widens on one side only, as the paper's algorithm states it: the
+    left siblings if the node has any (even empty ones), else the right ones;
   * a starving sub-tree is served by starting the search at that node: the
     non-empty internal node with the largest age above the threshold (ties:
     the deeper, then the leftmost node); the node where a search ends and all
@@ -45,8 +47,8 @@ emitted exactly once).
 """
 from __future__ import annotations
 
-from dataclasses import dataclass, field
-from typing import List, Optional
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Tuple
 
 
 @dataclass
@@ -56,19 +58,53 @@ class Request:
     blocks: int
 
 
-@dataclass
-class Node:
+@dataclass(frozen=True)
+class Span:
+    """A node of the quad-tree, named by the inclusive range of prefix lengths
+    it covers.  The tree is implicit: a span of width w > leaf_width has four
+    children of width w / 4; the root is [1, max_len]."""
     lo: int
-    hi: int                      # inclusive range of prefix lengths
-    depth: int
-    parent: Optional["Node"] = None
-    slot: int = 0                # index among the parent's children
-    children: List["Node"] = field(default_factory=list)   # empty for a leaf
-    requests: List[Request] = field(default_factory=list)  # leaves only
-    last_served: float = 0.0
+    hi: int
+    max_len: int
+    leaf_width: int
+
+    @property
+    def width(self) -> int:
+        return self.hi - self.lo + 1
 
     def is_leaf(self) -> bool:
-        return not self.children
+        return self.width == self.leaf_width
+
+    @property
+    def depth(self) -> int:
+        d, w = 0, self.max_len
+        while w > self.width:
+            w //= 4
+            d += 1
+        return d
+
+    @property
+    def children(self) -> List["Span"]:
+        if self.is_leaf():
+            return []
+        q = self.width // 4
+        return [Span(self.lo + i * q, self.lo + (i + 1) * q - 1, self.max_len, self.leaf_width) for i in range(4)]
+
+    @property
+    def parent(self) -> Optional["Span"]:
+        if self.width == self.max_len:
+            return None
+        w = self.width * 4
+        lo = 1 + (self.lo - 1) // w * w
+        return Span(lo, lo + w - 1, self.max_len, self.leaf_width)
+
+    @property
+    def slot(self) -> int:
+        """Position among the parent's four children (0 = leftmost)."""
+        return (self.lo - 1) // self.width % 4
+
+    def holds(self, length: int) -> bool:
+        return self.lo <= length <= self.hi
 
 
 class QuadTree:
@@ -84,148 +120,126 @@ class QuadTree:
             raise ValueError("max_len / leaf_width must be a power of four")
         self.max_len = max_len
         self.leaf_width = leaf_width
-        self.root = self._build(1, max_len, 0, None, 0)
-        self._by_id = {}
+        self.root = Span(1, max_len, max_len, leaf_width)
+        self.table: Dict[int, Request] = {}              # every request in the tree, by id
+        self.served: Dict[Tuple[int, int], float] = {}   # (lo, hi) of a node -> time stamp (Section 3.5)
         self.last_case = None        # 1, 2 (leaf overflow) or 3: how the last batch ended
-        self.last_node = None
+        self.last_node: Optional[Span] = None
 
-    def _build(self, lo, hi, depth, parent, slot) -> Node:
-        n = Node(lo=lo, hi=hi, depth=depth, parent=parent, slot=slot)
-        width = hi - lo + 1
-        if width > self.leaf_width:
-            q = width // 4
-            n.children = [self._build(lo + i * q, lo + (i + 1) * q - 1, depth + 1, n, i) for i in range(4)]
-        return n
-
-    # -- bookkeeping ------------------------------------------------------
+    # -- the table and the counters derived from it ------------------------
     def clamp(self, length: int) -> int:
         return max(1, min(int(length), self.max_len))
 
+    def collect(self, node: Span) -> List[Request]:
+        """The requests whose key falls in the node's range, in ascending (length, id)."""
+        return sorted((r for r in self.table.values() if node.holds(r.length)), key=lambda r: (r.length, r.id))
+
+    def request_counter(self, node: Span) -> int:
+        return len(self.collect(node))
+
+    def block_counter(self, node: Span) -> int:
+        return sum(r.blocks for r in self.collect(node))
+
+    def _path(self, key: int) -> List[Span]:
+        """Root-to-leaf chain of the nodes whose range holds `key`."""
+        chain, node = [self.root], self.root
+        while not node.is_leaf():
+            node = next(c for c in node.children if c.holds(key))
+            chain.append(node)
+        return chain
+
     def insert(self, rid: int, length: int, blocks: int, now: float = 0.0) -> None:
-        if rid in self._by_id:
+        if rid in self.table:
             raise ValueError(f"request {rid} is already in the tree")
         if blocks < 1 or length < 1:
             raise ValueError("length and blocks must be positive")
         key = self.clamp(length)
-        node = self.root
-        while True:
+        for node in self._path(key):
             if self.request_counter(node) == 0:
-                node.last_served = now       # age counts from the first arrival
-            if node.is_leaf():
-                break
-            q = (node.hi - node.lo + 1) // 4
-            node = node.children[(key - node.lo) // q]
-        r = Request(rid, key, int(blocks))
-        node.requests.append(r)
-        self._by_id[rid] = (r, node)
+                self.served[(node.lo, node.hi)] = now    # age counts from the first arrival
+        self.table[rid] = Request(rid, key, int(blocks))
 
     def remove(self, rid: int) -> None:
-        r, leaf = self._by_id.pop(rid)
-        leaf.requests.remove(r)
+        del self.table[rid]
 
     def __len__(self) -> int:
-        return len(self._by_id)
+        return len(self.table)
 
-    def collect(self, node: Node) -> List[Request]:
-        """CollectRequests: the sub-tree's requests in ascending (length, id)."""
-        if node.is_leaf():
-            return sorted(node.requests, key=lambda r: (r.length, r.id))
-        out: List[Request] = []
-        for c in node.children:
-            out.extend(self.collect(c))
-        return out
+    # -- one batch (Section 3.3) --------------------------------------------
+    def _widen(self, node: Span, budget: int, want: int) -> List[Request]:
+        """Case 3: up to `want` requests of the node's siblings, nearest in prefix length first,
+        ending at the first one whose blocks no longer fit `budget`."""
+        parent = node.parent
+        if parent is None:
+            return []
+        family = self.collect(parent)
+        if node.slot > 0:      # there are siblings to the left: only they are searched, longest first
+            pool = [r for r in reversed(family) if r.length < node.lo]
+        else:                  # leftmost child: the siblings to the right, shortest first
+            pool = [r for r in family if r.length > node.hi]
+        taken: List[Request] = []
+        for r in pool:
+            if len(taken) == want or r.blocks > budget:
+                break
+            taken.append(r)
+            budget -= r.blocks
+        return taken
 
-    def request_counter(self, node: Node) -> int:
-        return len(self.collect(node))
-
-    def block_counter(self, node: Node) -> int:
-        return sum(r.blocks for r in self.collect(node))
-
-    # -- Algorithm 1 ------------------------------------------------------
-    def recursive_dfs(self, node: Node, b_max: int, k_min: int) -> List[Request]:
-        batch = self.collect(node)
-        b_used = sum(r.blocks for r in batch)
-        if b_used <= b_max and len(batch) >= k_min:                    # case 1
-            self.last_case, self.last_node = 1, node
-            return batch
-        if b_used > b_max:                                              # case 2
-            if node.is_leaf():
-                taken, used = [], 0
-                for r in batch:          # the first request is always taken
-                    if taken and used + r.blocks > b_max:
+    def _search(self, node: Span, b_max: int, k_min: int) -> List[Request]:
+        while True:
+            own = self.collect(node)
+            load = sum(r.blocks for r in own)
+            if load > b_max and not node.is_leaf():
+                # case 2: too many blocks here -> the child that holds the most requests (leftmost on ties)
+                node = max(node.children, key=lambda c: (self.request_counter(c), -c.lo))
+                continue
+            self.last_node = node
+            if load > b_max:
+                # case 2 with nothing below: requests in order while they fit, never fewer than one
+                self.last_case = 2
+                batch, room = [], b_max
+                for r in own:
+                    if batch and r.blocks > room:
                         break
-                    taken.append(r)
-                    used += r.blocks
-                self.last_case, self.last_node = 2, node
-                return taken
-            counts = [self.request_counter(c) for c in node.children]
-            c_max = node.children[counts.index(max(counts))]
-            return self.recursive_dfs(c_max, b_max, k_min)
-        b_left = b_max - b_used                                         # case 3
-        k_left = k_min - len(batch)
-        addition: List[Request] = []
-        if node.parent is not None:
-            sibs = node.parent.children
-            left, right = sibs[:node.slot], sibs[node.slot + 1:]
-            if left:
-                addition = self.r_search(left, b_left, k_left)
-            else:
-                addition = self.l_search(right, b_left, k_left)
-        self.last_case, self.last_node = 3, node
-        return batch + addition[:min(k_left, len(addition))]
+                    batch.append(r)
+                    room -= r.blocks
+                return batch
+            if len(own) >= k_min:
+                self.last_case = 1                       # case 1: fits and is large enough
+                return own
+            self.last_case = 3                           # case 3: fits but is too small
+            return own + self._widen(node, b_max - load, k_min - len(own))
 
-    def r_search(self, siblings: List[Node], b_left: int, k_left: int) -> List[Request]:
-        selected: List[Request] = []
-        for s in reversed(siblings):                       # right to left: nearest first
-            for r in reversed(self.collect(s)):            # longest (nearest) first
-                if r.blocks + sum(x.blocks for x in selected) <= b_left:
-                    selected.append(r)
-                else:
-                    return selected
-        return selected
-
-    def l_search(self, siblings: List[Node], b_left: int, k_left: int) -> List[Request]:
-        selected: List[Request] = []
-        for s in siblings:                                 # left to right: nearest first
-            for r in self.collect(s):                      # shortest (nearest) first
-                if r.blocks + sum(x.blocks for x in selected) <= b_left:
-                    selected.append(r)
-                else:
-                    return selected
-        return selected
-
-    # -- batch generation --------------------------------------------------
-    def _internal_nodes(self, node: Node):
-        if node.is_leaf():
-            return
-        yield node
-        for c in node.children:
-            yield from self._internal_nodes(c)
+    def _starving(self, now: float, threshold: float) -> Optional[Span]:
+        """The non-empty internal node that has waited longest beyond the threshold
+        (ties: the deeper one, then the leftmost)."""
+        seen, best = set(), None
+        for r in self.table.values():
+            for node in self._path(r.length)[:-1]:       # internal nodes only
+                if (node.lo, node.hi) in seen:
+                    continue
+                seen.add((node.lo, node.hi))
+                age = now - self.served.get((node.lo, node.hi), 0.0)
+                if age > threshold:
+                    rank = (age, node.depth, -node.lo)
+                    if best is None or rank > best[0]:
+                        best = (rank, node)
+        return None if best is None else best[1]
 
     def next_batch(self, b_max: int, k_min: int, now: float = 0.0,
                    starve_after: Optional[float] = None) -> List[int]:
         """Generate one batch, remove its requests from the tree, return their
         ids in emission order ([] when the tree is empty)."""
-        if len(self) == 0:
+        if not self.table:
             return []
         start = self.root
         if starve_after is not None:
-            best = None
-            for n in self._internal_nodes(self.root):
-                if self.request_counter(n) == 0:
-                    continue
-                age = now - n.last_served
-                if age > starve_after:
-                    key = (age, n.depth, -n.lo)
-                    if best is None or key > best[0]:
-                        best = (key, n)
-            if best is not None:
-                start = best[1]
-        batch = self.recursive_dfs(start, b_max, k_min)
-        n = self.last_node
-        while n is not None:
-            n.last_served = now
-            n = n.parent
+            start = self._starving(now, starve_after) or self.root
+        batch = self._search(start, b_max, k_min)
+        node = self.last_node
+        while node is not None:                          # the node where the search ended, and its ancestors
+            self.served[(node.lo, node.hi)] = now
+            node = node.parent
         for r in batch:
             self.remove(r.id)
         return [r.id for r in batch]

@@ -991,27 +991,54 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict_
                                                       const float* __restrict__ part_acc,
                                                       char* __restrict__ out, int batch, int Hq,
                                                       int out_dtype) {
-  constexpr int LPP = D / 4;
+  constexpr int LPP = D / 4;  // lanes per (request, head): an aligned group inside one wavefront
   const int pair = blockIdx.x * (256 / LPP) + threadIdx.x / LPP;
   const int sub = threadIdx.x % LPP;
-  if (pair >= batch * Hq) return;
+  if (pair >= batch * Hq) return;  // the whole lane group leaves together
   const int b = pair / Hq;
   const int hq = pair - b * Hq;
   const int first = use_inline ? icu.first[b] : cu_chunks[b];
   const int n = (use_inline ? icu.first[b + 1] : cu_chunks[b + 1]) - first;
   if (n <= 1) return;  // finished by the attention kernel itself
-  float M = kNegInf;
-  for (int i = 0; i < n; ++i) M = fmaxf(M, part_ml[static_cast<size_t>(first + i) * Hq + hq].x);
-  float l = 0.f;
+  // Few dependent memory round trips instead of one per chunk: lane `sub` fetches (m, l) of chunk
+  // `sub`, the group's maximum and weights come from cross-lane steps, and the accumulator rows are
+  // requested eight at a time before any of them is used.  More than LPP chunks: further rounds,
+  // rescaled like an online softmax.
+  float M = kNegInf, l = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int i = 0; i < n; ++i) {
-    const size_t pi = static_cast<size_t>(first + i) * Hq + hq;
-    const float2 ml = part_ml[pi];
-    const float f = fast_exp2(ml.x - M);
-    const float4 v = *reinterpret_cast<const float4*>(part_acc + pi * D + sub * 4);
-    l = fmaf(ml.y, f, l);
-    acc.x = fmaf(v.x, f, acc.x); acc.y = fmaf(v.y, f, acc.y);
-    acc.z = fmaf(v.z, f, acc.z); acc.w = fmaf(v.w, f, acc.w);
+  for (int base = 0; base < n; base += LPP) {
+    const int cnt = min(n - base, LPP);
+    const bool have = sub < cnt;
+    const float2 ml = have ? part_ml[static_cast<size_t>(first + base + sub) * Hq + hq] : make_float2(kNegInf, 0.f);
+    float mx = ml.x;
+#pragma unroll
+    for (int off = LPP / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, LPP));
+    const float Mn = fmaxf(M, mx);                    // finite: every chunk holds at least one token
+    const float resc = fast_exp2(M - Mn);             // 0 in the first round (M = -inf)
+    acc.x *= resc; acc.y *= resc; acc.z *= resc; acc.w *= resc;
+    l *= resc;
+    M = Mn;
+    const float f = have ? fast_exp2(ml.x - M) : 0.f;
+    float lw = ml.y * f;
+#pragma unroll
+    for (int off = LPP / 2; off > 0; off >>= 1) lw += __shfl_xor(lw, off, LPP);
+    l += lw;
+    for (int j0 = 0; j0 < cnt; j0 += 8) {
+      float4 v[8];
+      float fj[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int jc = min(j0 + u, cnt - 1);          // clamped: rows past the end get weight 0
+        const float w = __shfl(f, jc, LPP);
+        fj[u] = (j0 + u < cnt) ? w : 0.f;
+        v[u] = *reinterpret_cast<const float4*>(part_acc + (static_cast<size_t>(first + base + jc) * Hq + hq) * D + sub * 4);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        acc.x = fmaf(v[u].x, fj[u], acc.x); acc.y = fmaf(v[u].y, fj[u], acc.y);
+        acc.z = fmaf(v[u].z, fj[u], acc.z); acc.w = fmaf(v[u].w, fj[u], acc.w);
+      }
+    }
   }
   const float inv = 1.f / l;
   const size_t oi = (static_cast<size_t>(b) * Hq + hq) * D + sub * 4;
