@@ -637,7 +637,7 @@ def main():
 
     if not args.skip_extra:
         # ---------------- per-batch times, aligned vs random
-        def per_batch(batches, reps=9):
+        def per_batch(batches, reps=9, fn=None):
             """Every batch timed inside passes over all of them (31.6 GB cycled: nothing is re-read from
             the 256 MB Infinity Cache, as it would be if one small batch were launched back to back);
             median over the passes.  The event pair around a launch adds about 1.7 us to it."""
@@ -645,7 +645,7 @@ def main():
             for r in range(reps):
                 for i, b in enumerate(batches):
                     ev[r][i].record()
-                    attend(b)
+                    (fn or attend)(b)
                 ev[r][-1].record()
             torch.cuda.synchronize()
             rows = []
@@ -657,6 +657,13 @@ def main():
             return rows
 
         rows_a = per_batch(batches_a)
+        # the same launches with the library's read-only sweep (same plan, same loads, XOR instead of
+        # attention, one word stored per workgroup): what a launch of that size costs on this machine
+        sweep_rows = per_batch(batches_a, fn=lambda b: als.kv_read_sweep(pool.k, pool.v, b.block_table, b.kv_lens, None,
+                                                                         b.params, ws, kv_lens_host=b.kv_lens_host))
+        for ra, rs in zip(rows_a, sweep_rows):
+            ra["sweep_us"] = rs["us"]
+            ra["pct_of_sweep"] = round(100.0 * rs["us"] / ra["us"], 1)
         for _ in range(2):
             step_random()
         # per-pass times, median: a single disturbed pass must not decide the comparison

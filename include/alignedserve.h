@@ -382,7 +382,10 @@ as_status as_pipeline_destroy(as_pipeline* p);
  * checksum: device uint32[256], XOR-accumulated (slot = workgroup index mod
  * 256, folded in by a second small kernel); the XOR of the 256 slots equals
  * the XOR of every 32-bit word of every K and V block the batch references
- * (whole blocks), for the slots' initial contents zero.  Same errors as
+ * (whole blocks), for the slots' initial contents zero.  checksum may be null:
+ * the folding kernel is then left out and the call is a single launch, the
+ * read-only counterpart of an attention call on a batch that is not split
+ * (what the per-launch cost of such a call is compared with).  Same errors as
  * as_decode_attention.
  * -------------------------------------------------------------------------- */
 as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks,

@@ -283,7 +283,8 @@ def kv_read_sweep(k_blocks, v_blocks, block_table, kv_lens, checksum, params: At
     """Measurement aid: stream the K/V bytes the attention call would read."""
     host = None if kv_lens_host is None else _i32(kv_lens_host)
     _check(load().as_kv_read_sweep(k_blocks.data_ptr(), v_blocks.data_ptr(), block_table.data_ptr(),
-                                   kv_lens.data_ptr(), _ptr(host, C.c_int32), checksum.data_ptr(),
+                                   kv_lens.data_ptr(), _ptr(host, C.c_int32),
+                                   None if checksum is None else checksum.data_ptr(),
                                    C.byref(params), workspace.data_ptr(), workspace.numel(),
                                    _stream_ptr(stream)))
 
