@@ -676,7 +676,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnArgs a, InlinePlan i
 // The sum l is accumulated from the fp32 probabilities.
 constexpr int kLdsRow = 272;                    // 256 B of a K row + 16 B pad
 constexpr int kLdsKTile = kBlock * kLdsRow;     // per wave
-constexpr int kMfmaHeads = 16;
+constexpr int kMfmaHeads = 16;      // query heads per MFMA column block
+#ifndef AS_MFMA_MAX_HEADS
+#define AS_MFMA_MAX_HEADS 32
+#endif
+constexpr int kMfmaMaxHeads = AS_MFMA_MAX_HEADS;  // query heads one workgroup serves (1 or 2 column blocks)
 
 // The two 16-bit element types differ only in the MFMA opcodes and in how
 // probabilities are rounded to the element type and widened back.
@@ -719,10 +723,15 @@ template <> struct Mfma<f16_t> {
   }
 };
 
-template <typename T, bool MASKED>
+// One tile for NG groups of 16 query heads: the K tile goes through LDS once
+// and each A operand read from it feeds NG MFMAs (one per head group); the V
+// halves are gathered once and feed NG x 4 MFMAs.  Only the softmax state and
+// the probabilities exist per group, so a workgroup of 32 heads reads the K/V
+// stream once where two workgroups of 16 would read it twice.
+template <typename T, bool MASKED, int NG>
 __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr)[4],
-                                          const u32x4 (&qb)[4], char* lds, f32x4 (&acc)[8],
-                                          float& m_run, float& l_run, float c, int first_token,
+                                          const u32x4 (&qb)[NG][4], char* lds, f32x4 (&acc)[NG][8],
+                                          float (&m_run)[NG], float (&l_run)[NG], float c, int first_token,
                                           int kv_len, int lane) {
   const int col = lane & 15;
   const int rg = lane >> 4;
@@ -731,49 +740,58 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
   for (int i = 0; i < 4; ++i)
     *reinterpret_cast<u32x4*>(lds + (4 * rg + i) * kLdsRow + col * 16) = kr[i];
   __builtin_amdgcn_wave_barrier();
-  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  f32x4 s[NG];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) s[g] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const u32x4 ku = *reinterpret_cast<const u32x4*>(lds + col * kLdsRow + (4 * j + rg) * 16);
-    s = Mfma<T>::qk(ku, qb[j], s);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) s[g] = Mfma<T>::qk(ku, qb[g][j], s[g]);
   }
   __builtin_amdgcn_wave_barrier();
 
-  float sv[4] = {s.x, s.y, s.z, s.w};
   bool valid[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    valid[i] = !MASKED || (first_token + 4 * i + rg < kv_len);
-    if (MASKED) sv[i] = valid[i] ? sv[i] : kNegInf;
-  }
-  float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));           // max over the tile's 16 tokens, per head
-  const float m_new = fmaxf(m_run, mx);          // finite: a tile has at least one valid token
-  const float alpha = fast_exp2((m_run - m_new) * c);
-  const float nref = -m_new * c;
-  float p[4];
+  for (int i = 0; i < 4; ++i) valid[i] = !MASKED || (first_token + 4 * i + rg < kv_len);
+
+  u32x2 pB[NG], pB2[NG];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    p[i] = fast_exp2(fmaf(sv[i], c, nref));
-    if (MASKED) p[i] = valid[i] ? p[i] : 0.f;
-  }
-  const uint32_t w01 = Mfma<T>::pack(p[0], p[1]);
-  const uint32_t w23 = Mfma<T>::pack(p[2], p[3]);
-  // second term of the two-term representation p = hi + lo (each in the
-  // element type): the matrix cores have cycles to spare next to the K/V
-  // stream, and two terms carry 16 (bf16) or 22 (fp16) bits of the fp32 weight
-  const uint32_t x01 = Mfma<T>::pack(p[0] - Mfma<T>::first(w01), p[1] - Mfma<T>::second(w01));
-  const uint32_t x23 = Mfma<T>::pack(p[2] - Mfma<T>::first(w23), p[3] - Mfma<T>::second(w23));
-  const float psum = (p[0] + p[1]) + (p[2] + p[3]);
-  l_run = fmaf(l_run, alpha, psum);
-  m_run = m_new;
-  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+  for (int g = 0; g < NG; ++g) {
+    float sv[4] = {s[g].x, s[g].y, s[g].z, s[g].w};
+    if (MASKED) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+      for (int i = 0; i < 4; ++i) sv[i] = valid[i] ? sv[i] : kNegInf;
+    }
+    float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));           // max over the tile's 16 tokens, per head
+    const float m_new = fmaxf(m_run[g], mx);       // finite: a tile has at least one valid token
+    const float alpha = fast_exp2((m_run[g] - m_new) * c);
+    const float nref = -m_new * c;
+    float p[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      p[i] = fast_exp2(fmaf(sv[i], c, nref));
+      if (MASKED) p[i] = valid[i] ? p[i] : 0.f;
+    }
+    const uint32_t w01 = Mfma<T>::pack(p[0], p[1]);
+    const uint32_t w23 = Mfma<T>::pack(p[2], p[3]);
+    // second term of the two-term representation p = hi + lo (each in the
+    // element type): the matrix cores have cycles to spare next to the K/V
+    // stream, and two terms carry 16 (bf16) or 22 (fp16) bits of the fp32 weight
+    const uint32_t x01 = Mfma<T>::pack(p[0] - Mfma<T>::first(w01), p[1] - Mfma<T>::second(w01));
+    const uint32_t x23 = Mfma<T>::pack(p[2] - Mfma<T>::first(w23), p[3] - Mfma<T>::second(w23));
+    const float psum = (p[0] + p[1]) + (p[2] + p[3]);
+    l_run[g] = fmaf(l_run[g], alpha, psum);
+    m_run[g] = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
+    }
+    pB[g] = u32x2{w01, w23};
+    pB2[g] = u32x2{x01, x23};
   }
-  const u32x2 pB = {w01, w23};
-  const u32x2 pB2 = {x01, x23};
 
   // V: gather the 16-bit halves of the 4 tokens for each of the lane's 8 dims
   u32x4 v0 = vr[0], v1 = vr[1], v2 = vr[2], v3 = vr[3];
@@ -792,17 +810,21 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
                       __builtin_amdgcn_perm(a3[w], a2[w], 0x05040100u)};
     const u32x2 hi = {__builtin_amdgcn_perm(a1[w], a0[w], 0x07060302u),
                       __builtin_amdgcn_perm(a3[w], a2[w], 0x07060302u)};
-    acc[2 * w] = Mfma<T>::pv(lo, pB, acc[2 * w]);
-    acc[2 * w + 1] = Mfma<T>::pv(hi, pB, acc[2 * w + 1]);
-    acc[2 * w] = Mfma<T>::pv(lo, pB2, acc[2 * w]);
-    acc[2 * w + 1] = Mfma<T>::pv(hi, pB2, acc[2 * w + 1]);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      acc[g][2 * w] = Mfma<T>::pv(lo, pB[g], acc[g][2 * w]);
+      acc[g][2 * w + 1] = Mfma<T>::pv(hi, pB[g], acc[g][2 * w + 1]);
+      acc[g][2 * w] = Mfma<T>::pv(lo, pB2[g], acc[g][2 * w]);
+      acc[g][2 * w + 1] = Mfma<T>::pv(hi, pB2[g], acc[g][2 * w + 1]);
+    }
   }
 }
 
-// G = query heads per workgroup (<= 16), D = 128, T = bf16_t or f16_t.
-template <typename T>
+// G = query heads per workgroup (<= 16 * NG), D = 128, T = bf16_t or f16_t.
+template <typename T, int NG>
 __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, InlinePlan ip) {
   constexpr int D = 128;
+  constexpr int kHeads = kMfmaHeads * NG;
   constexpr size_t kSlabBytes = static_cast<size_t>(kBlock) * D * 2;
   // the K transpose tiles (loop) and the cross-wave merge buffers (epilogue)
   // share one allocation; a barrier separates the two uses
@@ -810,10 +832,10 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   // consecutive output dimensions then fall on distinct banks across the 8
   // lanes (neighbouring heads) that one LDS cycle serves
   constexpr int kMergeRow = D + 4;
-  constexpr int kMergeBytes = kWaves * kMfmaHeads * kMergeRow * 4;
+  constexpr int kMergeBytes = kWaves * kHeads * kMergeRow * 4;
   __shared__ __attribute__((aligned(16))) char smem[kMergeBytes];
-  __shared__ float sm_m[kWaves][kMfmaHeads];
-  __shared__ float sm_l[kWaves][kMfmaHeads];
+  __shared__ float sm_m[kWaves][kHeads];
+  __shared__ float sm_l[kWaves][kHeads];
   static_assert(kWaves * kLdsKTile <= kMergeBytes, "K tiles must fit the shared buffer");
 
   const int Hkv = a.num_kv_heads;
@@ -862,23 +884,32 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   const bool single = kv_len <= a.chunk;
   const int my_tiles = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
 
-  // Q^T operand: head `col`, dims 8*(4j+rg) .. +8 for MFMA j; zero past G
-  u32x4 qb[4];
+  // Q^T operands: group g, head 16*g + col, dims 8*(4j+rg) .. +8 for MFMA j; zero past G
+  u32x4 qb[NG][4];
   {
     const u32x4 zero = {0u, 0u, 0u, 0u};
-    const char* qrow = a.q + (static_cast<size_t>(b) * Hq + hg * G + (col < G ? col : 0)) * D * 2;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      u32x4 w = *reinterpret_cast<const u32x4*>(qrow + (4 * j + rg) * 16);
-      w = col < G ? w : zero;
-      qb[j] = w;
+    for (int g = 0; g < NG; ++g) {
+      const int head = kMfmaHeads * g + col;
+      const char* qrow = a.q + (static_cast<size_t>(b) * Hq + hg * G + (head < G ? head : 0)) * D * 2;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        u32x4 w = *reinterpret_cast<const u32x4*>(qrow + (4 * j + rg) * 16);
+        w = head < G ? w : zero;
+        qb[g][j] = w;
+      }
     }
   }
 
-  f32x4 acc[8];
+  f32x4 acc[NG][8];
+  float m_run[NG], l_run[NG];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = kNegInf, l_run = 0.f;
+  for (int g = 0; g < NG; ++g) {
+    m_run[g] = kNegInf;
+    l_run[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[g][e] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   const float c = a.c;
   char* lds = smem + wave * kLdsKTile;
   const size_t head_off = static_cast<size_t>(h) * kSlabBytes;
@@ -905,13 +936,13 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
       load_tile<T, D>(kB, a.k_blocks + off, lane);
       load_tile<T, D>(vB, a.v_blocks + off, lane);
     }
-    mfma_tile<T, false>(kA, vA, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
+    mfma_tile<T, false, NG>(kA, vA, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
     if (i + 2 < my_tiles) {
       const size_t off = tile_off(i + 2);
       load_tile<T, D>(kA, a.k_blocks + off, lane);
       load_tile<T, D>(vA, a.v_blocks + off, lane);
     }
-    mfma_tile<T, false>(kB, vB, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
+    mfma_tile<T, false, NG>(kB, vB, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
   }
   if (i < my_tiles) {
     const bool haveB = i + 1 < my_tiles;
@@ -920,28 +951,35 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
       load_tile<T, D>(kB, a.k_blocks + off, lane);
       load_tile<T, D>(vB, a.v_blocks + off, lane);
     }
-    mfma_tile<T, true>(kA, vA, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * i) * kBlock, kv_len, lane);
+    mfma_tile<T, true, NG>(kA, vA, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * i) * kBlock, kv_len, lane);
     if (haveB)
-      mfma_tile<T, true>(kB, vB, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * (i + 1)) * kBlock, kv_len, lane);
+      mfma_tile<T, true, NG>(kB, vB, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * (i + 1)) * kBlock, kv_len, lane);
   }
 
   // each row group summed its own 4 tokens per tile; m is already common
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    l_run[g] += __shfl_xor(l_run[g], 16);
+    l_run[g] += __shfl_xor(l_run[g], 32);
+  }
 
   __syncthreads();  // every wave is done with its K tile: the buffer becomes merge space
   float* sm_o = reinterpret_cast<float*>(smem);  // [wave][head][kMergeRow]
-  if (col < G) {
-    if (rg == 0) { sm_m[wave][col] = m_run; sm_l[wave][col] = l_run; }
-    // register i of accumulator e is dimension 32*rg + 8*i + e: the lane owns
-    // 32 consecutive dimensions of head `col`, written as 8 float4
-    float* row = sm_o + (wave * kMfmaHeads + col) * kMergeRow + 32 * rg;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const f32x4 lo4 = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-      const f32x4 hi4 = {acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
-      *reinterpret_cast<f32x4*>(row + 8 * i) = lo4;
-      *reinterpret_cast<f32x4*>(row + 8 * i + 4) = hi4;
+  for (int g = 0; g < NG; ++g) {
+    const int head = kMfmaHeads * g + col;
+    if (head < G) {
+      if (rg == 0) { sm_m[wave][head] = m_run[g]; sm_l[wave][head] = l_run[g]; }
+      // register i of accumulator e is dimension 32*rg + 8*i + e: the lane owns
+      // 32 consecutive dimensions of its head, written as 8 float4
+      float* row = sm_o + (wave * kHeads + head) * kMergeRow + 32 * rg;
+#pragma unroll
+      for (int i2 = 0; i2 < 4; ++i2) {
+        const f32x4 lo4 = {acc[g][0][i2], acc[g][1][i2], acc[g][2][i2], acc[g][3][i2]};
+        const f32x4 hi4 = {acc[g][4][i2], acc[g][5][i2], acc[g][6][i2], acc[g][7][i2]};
+        *reinterpret_cast<f32x4*>(row + 8 * i2) = lo4;
+        *reinterpret_cast<f32x4*>(row + 8 * i2 + 4) = hi4;
+      }
     }
   }
   __syncthreads();
@@ -957,7 +995,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
     for (int w = 0; w < kWaves; ++w) {
       const float f = fast_exp2((sm_m[w][g] - M) * c);
       l = fmaf(sm_l[w][g], f, l);
-      o = fmaf(sm_o[(w * kMfmaHeads + g) * kMergeRow + d], f, o);
+      o = fmaf(sm_o[(w * kHeads + g) * kMergeRow + d], f, o);
     }
     const int hq = hg * G + g;
     if (single) {
@@ -1145,7 +1183,8 @@ __global__ __launch_bounds__(256) void sweep_fold_kernel(const uint32_t* __restr
 // Which kernel serves these parameters and how many query heads one workgroup
 // takes.  Matrix-core path: 16-bit inputs, D = 128, grouped-query shapes where
 // the vector-ALU kernel is bound by its own arithmetic; one workgroup takes up
-// to 16 heads of a group, wider groups are cut into 16s or 8s.  Vector-ALU
+// to 32 heads of a group (two MFMA column blocks fed by one K/V read), wider
+// groups are cut into 32s, 16s or 8s.  Vector-ALU
 // path: the largest divisor of the group up to 8, so that one K/V read serves
 // as many heads as possible; what is left of a wider group is covered by
 // several workgroups reading the same KV head.
@@ -1156,7 +1195,8 @@ struct KernelChoice {
 KernelChoice choose_kernel(const as_attn_params& p) {
   const int group = p.num_q_heads / p.num_kv_heads;
   if (p.dtype != AS_DTYPE_F32 && p.head_dim == 128 && group >= 4 && !(p.flags & AS_ATTN_NO_MFMA)) {
-    if (group <= 16) return {true, group};
+    if (group <= kMfmaMaxHeads) return {true, group};       // the whole group: one read of the KV head
+    if (group % kMfmaMaxHeads == 0) return {true, kMfmaMaxHeads};
     if (group % 16 == 0) return {true, 16};
     if (group % 8 == 0) return {true, 8};
   }
@@ -1435,10 +1475,17 @@ as_status run_decode_attention(const char* what, const void* q, const void* k_bl
     a.head_groups = p->num_q_heads / mfma_heads;
     a.kv_div = group / mfma_heads;
     const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
-    if (p->dtype == AS_DTYPE_BF16)
-      hipLaunchKernelGGL(attn_mfma_kernel<bf16_t>, grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
-    else
-      hipLaunchKernelGGL(attn_mfma_kernel<f16_t>, grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+    if (mfma_heads <= kMfmaHeads) {
+      if (p->dtype == AS_DTYPE_BF16)
+        hipLaunchKernelGGL((attn_mfma_kernel<bf16_t, 1>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+      else
+        hipLaunchKernelGGL((attn_mfma_kernel<f16_t, 1>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+    } else {
+      if (p->dtype == AS_DTYPE_BF16)
+        hipLaunchKernelGGL((attn_mfma_kernel<bf16_t, 2>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+      else
+        hipLaunchKernelGGL((attn_mfma_kernel<f16_t, 2>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+    }
   } else {
     const int G = kc.heads;
     a.head_groups = p->num_q_heads / G;

@@ -30,11 +30,11 @@ def uses_matrix_core(dtype: str, head_dim: int, num_q_heads: int, num_kv_heads: 
                      no_mfma: bool = False) -> bool:
     """The documented kernel-selection rule of as_decode_attention: 16-bit
     inputs, head_dim 128, at least 4 query heads per KV head, and a group that
-    is at most 16 or a multiple of 8."""
+    is at most 32 or a multiple of 8."""
     g = num_q_heads // num_kv_heads
     if dtype == "fp32" or head_dim != 128 or g < 4 or no_mfma:
         return False
-    return g <= 16 or g % 8 == 0
+    return g <= 32 or g % 8 == 0
 
 
 def kernel_bound(dtype: str, matrix_core: bool) -> float:

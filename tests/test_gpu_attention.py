@@ -180,7 +180,8 @@ def test_read_sweep_checksum_is_xor_of_referenced_blocks(lib):
     assert got == want
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (8, 1), (16, 1), (32, 2), (32, 1), (24, 1), (5, 1), (12, 1)])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (8, 1), (16, 1), (32, 2), (32, 1), (24, 1), (5, 1), (12, 1),
+                                    (17, 1), (64, 2), (64, 1), (40, 1), (96, 1), (48, 1)])
 def test_matrix_core_path_matches_oracle_and_vector_path(lib, Hq, Hkv):
     """bf16, D=128 grouped-query shapes: the MFMA kernel (default for groups
     >= 4) and the vector-ALU kernel (forced) both meet the bf16 tolerance."""
@@ -227,7 +228,7 @@ def test_randomised_shapes_against_oracle(lib):
         dtype = ["fp32", "bf16"][int(rng.integers(0, 2))]
         D = [64, 128][int(rng.integers(0, 2))]
         Hkv = int(rng.choice([1, 2, 3, 4, 8]))
-        G = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 16]))
+        G = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 16, 20, 32]))
         B = int(rng.integers(1, 24))
         hi = int(rng.choice([40, 300, 1500, 5000]))
         lens = rng.integers(1, hi + 1, B).astype(np.int32)

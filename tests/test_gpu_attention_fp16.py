@@ -44,7 +44,7 @@ def test_fp16_vector_kernel_matches_oracle(lib, D, Hq, Hkv):
             assert err <= TOL_VALU, f"max-abs err {err:.3e}"
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (16, 1), (32, 2), (24, 1), (5, 1), (12, 1)])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (16, 1), (32, 2), (24, 1), (5, 1), (12, 1), (32, 1), (64, 1), (29, 1)])
 def test_fp16_matrix_core_kernel_matches_oracle(lib, Hq, Hkv):
     for poison in ("nan", "big"):
         pb = wl.make_paged_batch(LENS, Hq, Hkv, 128, dtype="fp16", seed=Hq * 5 + Hkv, spare_blocks=2,

@@ -65,6 +65,8 @@ def test_kernel_selection_rule_helper():
     assert not pbnd.uses_matrix_core("bf16", 128, 6, 2)
     assert pbnd.uses_matrix_core("bf16", 128, 8, 2)
     assert pbnd.uses_matrix_core("fp16", 128, 64, 8)
-    assert pbnd.uses_matrix_core("bf16", 128, 24, 1)       # cut into groups of 8
-    assert not pbnd.uses_matrix_core("bf16", 128, 20, 1)   # neither <= 16 nor a multiple of 8
+    assert pbnd.uses_matrix_core("bf16", 128, 24, 1)       # one workgroup of 24 heads
+    assert pbnd.uses_matrix_core("bf16", 128, 20, 1)
+    assert pbnd.uses_matrix_core("bf16", 128, 40, 1)       # cut into groups of 8
+    assert not pbnd.uses_matrix_core("bf16", 128, 36, 1)   # neither <= 32 nor a multiple of 8
     assert not pbnd.uses_matrix_core("bf16", 128, 8, 1, no_mfma=True)
