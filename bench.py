@@ -558,14 +558,23 @@ def main():
         del src, dst
 
     # ---------------- headline: K timed steps over the aligned batches
-    # A process that starts within a few seconds of another GPU process's exit (the test suite, a
-    # previous bench) streams about 4 % slower for its first few hundred milliseconds; on an idle box
-    # it does not.  The same steps therefore run untimed for --settle-seconds before the W warm-up
-    # steps, so that the K timed steps measure the sustained rate either way.
+    # Device memory that was released a moment ago (by a process that has just exited -- the test
+    # suite, a previous bench -- or by a large free in this one) is cleared by the driver in the
+    # background, which takes a few per cent of the HBM bandwidth for some seconds.  The same steps
+    # therefore run untimed before the W warm-up steps until their rate is steady, so that the K
+    # timed steps measure the sustained rate either way.
+    # Untimed steps until the rate is steady: at least --settle-seconds, then until two consecutive
+    # groups of 10 steps agree within 0.2 % (at most 8 s in all).
     t_settle = time.perf_counter()
-    while time.perf_counter() - t_settle < args.settle_seconds:
-        step_aligned()
-        torch.cuda.synchronize()
+    prev, agree = None, 0
+    while args.settle_seconds > 0:
+        t_grp = time_region(step_aligned, 10, torch)
+        elapsed = time.perf_counter() - t_settle
+        agree = agree + 1 if prev is not None and abs(t_grp - prev) <= 0.002 * prev else 0
+        prev = t_grp
+        if (elapsed >= args.settle_seconds and agree >= 2) or elapsed > 8.0:
+            break
+    settle_s = time.perf_counter() - t_settle
     for _ in range(args.warmup):
         step_aligned()
     torch.cuda.synchronize()
@@ -618,6 +627,7 @@ def main():
                         "32 MHA heads x 128 bf16, block 16, 16 length-aligned batches of 64 per step",
             "device": dev_name, "seed": args.seed, "tokens_per_step": int(lens.sum()),
             "bytes_per_step": int(bytes_a), "chunk_tokens": args.chunk_tokens,
+            "settle_seconds": round(settle_s, 2),
         },
         "pct_of_peak": round(100 * value / HBM_PEAK_GBS, 1),
         "step_spread": {"ms_median": round(float(np.median(step_ms)), 4), "ms_p10": round(float(np.percentile(step_ms, 10)), 4),

@@ -209,3 +209,36 @@ def test_stage_policy_rejects_unknown_value(lib):
     from paper_2605_23389_amd import binding as als
     with pytest.raises(als.AlignedServeError):
         als.stage_set_policy(7)
+
+
+def test_pipeline_query_follows_the_copies(lib):
+    """as_pipeline_query polls a buffer's "ready" event from the host: complete before anything
+    was staged, not complete while the side stream is still busy ahead of the copies, complete
+    after they have finished -- and it never blocks."""
+    import time
+    import torch
+    from paper_2605_23389_amd import binding as als
+    block_bytes = 4096
+    host = _pinned((8, block_bytes), torch.uint8)
+    host.copy_(torch.arange(8 * block_bytes, dtype=torch.int64).remainder(251).to(torch.uint8).view(8, block_bytes))
+    dev = torch.zeros((8, block_bytes), dtype=torch.uint8, device="cuda")
+    pipe = als.Pipeline(2)
+    side = torch.cuda.ExternalStream(pipe.stream)
+    assert pipe.query(0) and pipe.query(1)                 # nothing staged yet
+    pipe.begin_stage(1)
+    with torch.cuda.stream(side):
+        torch.cuda._sleep(400_000_000)                     # keeps the side stream busy for a while
+    lib.stage_kv(host, None, np.arange(8, dtype=np.int64), dev, None, np.arange(8, dtype=np.int32), block_bytes,
+                 stream=pipe.stream)
+    pipe.end_stage(1)
+    t0 = time.perf_counter()
+    early = pipe.query(1)
+    assert time.perf_counter() - t0 < 0.05                 # a poll, not a wait
+    assert not early
+    assert pipe.query(0)                                   # the other buffer is unaffected
+    side.synchronize()
+    assert pipe.query(1)
+    assert torch.equal(dev.cpu(), host)
+    with pytest.raises(als.AlignedServeError):
+        pipe.query(2)
+    pipe.destroy()
