@@ -400,6 +400,35 @@ def cpu_baseline_leg(args, harness, traffic, pool, batches_a, Hq, Hkv, D, log):
     return out
 
 
+def wide_groups_leg(args, torch, als, harness, traffic, log, groups=(16, 24, 32, 64), reps=10):
+    """Grouped-query shapes beyond the benchmark configurations: 8 KV heads x G query heads each,
+    head_dim 128, bf16, 128 requests of 4096-8192 tokens (3.2 GB of KV per launch).  Up to 32 heads per
+    KV head one workgroup serves the whole group from a single read of the K/V stream."""
+    rows = {}
+    rng = np.random.default_rng(args.seed + 3)
+    lens = rng.integers(4096, 8193, 128).astype(np.int32)
+    for G in groups:
+        Hkv, Hq = 8, 8 * G
+        pool = harness.make_device_pool(lens, Hq, Hkv, 128, dtype="bf16", seed=args.seed + 12)
+        b = harness.make_device_batches(pool, np.arange(len(lens)), np.array([0, len(lens)]), seed=7)[0]
+        prm = als.attn_params(b.q, pool.k, b.block_table, b.out, chunk_tokens=args.chunk_tokens)
+        ws = torch.empty(als.decode_attention_workspace(prm, b.tokens), dtype=torch.uint8, device="cuda")
+
+        def f():
+            als.decode_attention(b.q, pool.k, pool.v, b.block_table, b.kv_lens, b.out,
+                                 kv_lens_host=b.kv_lens_host, workspace=ws, params=prm)
+        for _ in range(3):
+            f()
+        t = time_region(f, reps, torch) / reps
+        by = traffic.attention_bytes(lens, Hq, Hkv, 128, 2, 2)
+        rows[f"{G}_heads_per_kv_head"] = {"us": round(t * 1e6, 1), "GBs": round(by / t / 1e9, 0),
+                                          "pct_of_peak": round(by / t / 1e9 / HBM_PEAK_GBS * 100, 1)}
+    rows["note"] = ("8 KV heads x G query heads, D 128, bf16, 128 requests U{4096..8192}; algorithmic bytes count every "
+                    "K/V element once per KV head")
+    log(f"wide groups: {rows}")
+    return rows
+
+
 def decode_loop_leg(args, torch, als, wl, log, Hq, Hkv, D, n_sim=384):
     """Multi-iteration decode loop (Algorithm 2 every iteration, KV append + attention per
     iteration) on a block pool tight enough for evictions, for {prefix-aware, arrival-order}
@@ -447,6 +476,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--only-pipeline", action="store_true",
                     help="profiling aid: run only the scaled configs[4] staging/attention pipeline and print its line")
+    ap.add_argument("--only-wide-groups", default="",
+                    help="profiling aid: run only the grouped-query leg for these group sizes (e.g. 32 or 16,32,64)")
     ap.add_argument("--only-decode-loop", action="store_true",
                     help="run only the multi-iteration decode loop leg and print its line")
     ap.add_argument("--only-cfg3", action="store_true",
@@ -476,6 +507,11 @@ def main():
     if args.only_pipeline:
         print(json.dumps({"workload": "configs[4] host-resident KV pipeline (scaled)",
                           **pipeline_leg(args, torch, als, harness, traffic, wl, log)}), flush=True)
+        return
+    if args.only_wide_groups:
+        gs = tuple(int(x) for x in args.only_wide_groups.split(","))
+        print(json.dumps({"workload": "grouped-query shapes", **wide_groups_leg(
+            args, torch, als, harness, traffic, log, groups=gs, reps=max(args.steps, 1))}), flush=True)
         return
     if args.only_decode_loop:
         sh = wl.CONFIG_SHAPES[2]
@@ -890,6 +926,13 @@ def main():
                                                note="batch 128, 64 q heads / 8 kv heads, D 128, bf16, U{4096..32768}")
         log(f"cfg3: {rows3}")
         del pool3, b3
+
+        # ---------------- grouped-query shapes wider than the configurations use
+        try:
+            result["wide_groups"] = wide_groups_leg(args, torch, als, harness, traffic, log)
+        except Exception as e:
+            result["wide_groups"] = {"error": repr(e)}
+            log(f"wide-groups leg failed: {e!r}")
 
         # ---------------- multi-iteration decode loop: prefix-aware vs FCFS candidate batches,
         # candidate-buffer prefetch on vs off (the one-GPU analogue of the paper's time-to-schedule

@@ -57,6 +57,7 @@ class SimConfig:
     b_max_frac: float = 0.4          # paper Section 4.1: 40 % of the GPU blocks
     prefetch: bool = True            # stage candidates ahead of admission (off: stage when admitted)
     prefetch_group_blocks: int = 256 # blocks per prefetch copy group (a request is never cut)
+    prefetch_groups_in_flight: int = 2   # prefetch pauses while this many copy groups are unfinished
     stage_policy: str = "auto"       # how as_stage_kv moves blocks: "auto", "dma" or "kernel" (as_stage_set_policy)
     host_arena_blocks: int = 0       # 0 => one unique host block per logical block (verification runs)
     seed: int = 0
@@ -448,7 +449,7 @@ class DecodeSim:
         the candidate batch), as far as the candidate budget and the free blocks reach."""
         # Short groups, at most two in flight: the side stream is a FIFO, and an eviction or a copy
         # that an admission waits for must not queue behind tens of milliseconds of prefetch.
-        if self.be.outstanding() >= 2:
+        if self.be.outstanding() >= self.cfg.prefetch_groups_in_flight:
             return
         picks, need = [], 0
         for rid in self.r_cand + self.b_cand:
