@@ -71,3 +71,46 @@ def test_static_scratch_rejects_what_does_not_fit(lib):
     lib.decode_attention_static(q, k, k, bt, dl, out, kv_lens_host=np.full(B, L, dtype=np.int32), params=params)
     torch.cuda.synchronize()
     assert torch.all(out == 0.0)                              # V is all zeros
+
+
+def test_static_scratch_call_under_graph_capture(lib):
+    """The callers it exists for: one decode step (append + attention planned on the device, no
+    host lengths, no workspace) captured once and replayed while the lengths grow; every replay is
+    checked against the workspace entry point run eagerly on the same state."""
+    import torch
+    L0 = np.array([60, 126, 15, 255, 1, 700], dtype=np.int32)
+    R = 4
+    pb = wl.make_paged_batch(L0 + R, 8, 2, 128, dtype="bf16", seed=77, spare_blocks=1)
+    d = to_device(pb)
+    B = len(L0)
+    dl = torch.from_numpy(L0.copy()).cuda()
+    k_new = torch.empty((B, 2, 128), dtype=torch.bfloat16, device="cuda").normal_()
+    v_new = torch.empty_like(k_new).normal_()
+    out = torch.zeros(d["q"].shape, dtype=torch.float32, device="cuda")
+    ref = torch.zeros_like(out)
+    lib.decode_attention_static(d["q"], d["k"], d["v"], d["bt"], dl, out, chunk_tokens=64)   # looks the array up
+    torch.cuda.synchronize()
+
+    def step():
+        lib.kv_append(k_new, v_new, d["k"], d["v"], d["bt"], dl)
+        lib.decode_attention_static(d["q"], d["k"], d["v"], d["bt"], dl, out, chunk_tokens=64)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(R):
+        d["q"].normal_()
+        k_new.normal_()
+        v_new.normal_()
+        out.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        assert dl.cpu().numpy().tolist() == (L0 + r + 1).tolist()
+        lib.decode_attention(d["q"], d["k"], d["v"], d["bt"], dl, ref, chunk_tokens=64)      # eager, workspace
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), f"replay {r}"
+        assert torch.isfinite(out).all()
