@@ -438,18 +438,20 @@ def decode_loop_leg(args, torch, als, wl, log, Hq, Hkv, D, n_sim=384):
     prefix = wl.lognormal_lengths(rng, n_sim, 1024.0, 1.2, 64, 16384)
     outs = rng.integers(96, 289, n_sim).astype(np.int32)
     loop = {}
-    for policy in ("aligned", "fcfs"):
-        for prefetch in (True, False):
+    for policy, prefetch, starve in (("aligned", True, -1.0), ("aligned", False, -1.0), ("fcfs", True, -1.0),
+                                     ("fcfs", False, -1.0)):
+        if True:
             cfg = decode_sim.SimConfig(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, max_batch=64,
                                        hbm_blocks=6144, policy=policy, host_arena_blocks=4096,
-                                       evict_slots=16, seed=args.seed, prefetch=prefetch)
+                                       evict_slots=16, seed=args.seed, prefetch=prefetch, starve_after=starve)
             sim = decode_sim.DecodeSim(prefix, outs, cfg)
-            key = f"{policy}_prefetch_{'on' if prefetch else 'off'}"
+            key = f"{policy}_prefetch_{'on' if prefetch else 'off'}" + ("" if starve < 0 else f"_starve_after_{int(starve)}")
             loop[key] = decode_sim.summarize(sim.run())
             r = loop[key]
             log(f"decode loop {key}: {r['iterations']} it, attn p50/p99 {r['attn_us_p50']}/{r['attn_us_p99']} us, "
                 f"gap p50/p90/p99 {r['schedule_gap_us_p50']}/{r['schedule_gap_us_p90']}/{r['schedule_gap_us_p99']} us, "
-                f"{r['tokens_per_s']:.0f} tok/s, evictions {r['evictions']}")
+                f"{r['tokens_per_s']:.0f} tok/s, evictions {r['evictions']}, wait p50/p99/max "
+                f"{r['wait_iterations_p50']}/{r['wait_iterations_p99']}/{r['wait_iterations_max']} it")
             del sim
     loop["note"] = (f"{n_sim} requests, prefix lognormal(1024, s1.2) clip [64,16384], 96-288 output tokens, 7B-shaped "
                     "layer (one layer's KV per token), running batch <= 64 under a 6144-block HBM budget (768 MiB per "
@@ -457,7 +459,8 @@ def decode_loop_leg(args, torch, als, wl, log, Hq, Hkv, D, n_sim=384):
                     "pool; candidate batches from the quad-tree generator (K_min 36, B_max 40 %) vs arrival order; "
                     "schedule gap = end of an iteration's attention to the start of the next iteration's work on "
                     "the compute stream (host scheduling in Python + any wait for staging copies); prefetch off = "
-                    "a request is staged when Algorithm 2 admits it; tokens_per_s counts gaps and iterations")
+                    "a request is staged when Algorithm 2 admits it; tokens_per_s counts gaps and iterations; wait_iterations = "
+                    "decode iterations before a request is first admitted (all requests are in flight from the start)")
     return loop
 
 

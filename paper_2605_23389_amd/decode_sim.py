@@ -55,6 +55,8 @@ class SimConfig:
     policy: str = "aligned"          # "aligned" (quad-tree DFS) or "fcfs" (arrival order)
     k_min: int = 36                  # paper Section 4.1
     b_max_frac: float = 0.4          # paper Section 4.1: 40 % of the GPU blocks
+    starve_after: float = -1.0       # paper Section 3.5: a sub-tree that has waited longer than this many decode
+                                     # iterations is served first (negative: off)
     prefetch: bool = True            # stage candidates ahead of admission (off: stage when admitted)
     prefetch_group_blocks: int = 256 # blocks per prefetch copy group (a request is never cut)
     prefetch_groups_in_flight: int = 2   # prefetch pauses while this many copy groups are unfinished
@@ -342,6 +344,8 @@ class DecodeSim:
             for r in range(self.n):
                 self.tree.insert(r, int(self.prefix[r]), int(nblk[r]))
         self.origin = 0
+        self.iteration = 0                                        # decode iterations done: the loop's clock
+        self.first_admitted: Dict[int, int] = {}                  # rid -> iteration of its first admission
         self.run_ids = np.zeros(0, dtype=np.int32)
         self.stats = dict(attn_us=[], fwd_us=[], gap_us=[], batch_size=[], tokens=[], sched_ms=[], switching=0,
                           evictions=0, admissions=0, admitted_prefetched=0, admitted_resident=0, trace=[], completed=0, restored_blocks=0,
@@ -354,7 +358,8 @@ class DecodeSim:
         if self.tree is not None:
             if len(self.tree) == 0:
                 return False
-            ids, _ = self.tree.next_batch(self.b_max, cfg.k_min)
+            ids, _ = self.tree.next_batch(self.b_max, cfg.k_min, now=float(self.iteration),
+                                          starve_after=None if cfg.starve_after < 0 else cfg.starve_after)
         else:
             if not self.waiting:
                 return False
@@ -475,6 +480,7 @@ class DecodeSim:
             self.cand_used -= len(blocks)
             ticks[tick] = ticks.get(tick, 0) + (0 if rid in late else 1)
             self.blocks_of[rid] = blocks           # admission itself: the blocks change owner
+            self.first_admitted.setdefault(rid, self.iteration)
             self._row(rid, blocks)
             (self.b_cand if rid in self.b_cand else self.r_cand).remove(rid)
             self.stats["admissions"] += 1
@@ -561,7 +567,9 @@ class DecodeSim:
             if len(set(origins.tolist())) > 1:
                 self.stats["switching"] += 1
             it += 1
+            self.iteration = it
         self._reclaim(wait=True)
+        self.stats["wait_iterations"] = [self.first_admitted[r] for r in sorted(self.first_admitted)]
         self.be.finish(self.stats)
         return self.stats
 
@@ -584,6 +592,10 @@ def summarize(stats) -> dict:
         "completed": stats["completed"],
         "host_sched_ms_mean": round(float(np.mean(stats["sched_ms"])), 3),
     }
+    if stats.get("wait_iterations"):
+        w = np.asarray(stats["wait_iterations"])
+        out.update({"wait_iterations_p50": _pct(w, 50), "wait_iterations_p99": _pct(w, 99),
+                    "wait_iterations_max": int(w.max())})
     if stats["attn_us"]:
         us = np.asarray(stats["attn_us"])
         fwd = np.asarray(stats["fwd_us"])
