@@ -735,6 +735,30 @@ def main():
         }
         log(f"random: {gpu_r * 1e3:.3f} ms/pass vs aligned {gpu_s / args.steps * 1e3:.3f}")
 
+        # ---------------- the same random batches planned on the device (no host lengths: the form a
+        # captured HIP graph replays while lengths grow), launch sized for the worst case or for the
+        # caller's bound on the batch's blocks
+        dev_rows = {}
+        for label, with_bound in (("worst_case_grid", False), ("block_bound_grid", True)):
+            prms = [als.attn_params(b.q, pool.k, b.block_table, b.out, chunk_tokens=args.chunk_tokens,
+                                    total_blocks_bound=int(((b.kv_lens_host.astype(np.int64) + 15) // 16).sum())
+                                    if with_bound else 0) for b in batches_r]
+            ws_dev = torch.empty(max(als.decode_attention_workspace(p_, -1) for p_ in prms), dtype=torch.uint8,
+                                 device="cuda")
+
+            def step_dev():
+                for b, p_ in zip(batches_r, prms):
+                    als.decode_attention(b.q, pool.k, pool.v, b.block_table, b.kv_lens, b.out, workspace=ws_dev,
+                                         params=p_)
+            for _ in range(2):
+                step_dev()
+            t_dev = float(np.median([time_region(step_dev, 1, torch) for _ in range(7)]))
+            dev_rows[label] = {"ms_per_pass": round(t_dev * 1e3, 3), "GBs": round(bytes_r / t_dev / 1e9, 0)}
+        result["aligned_vs_random"]["random_device_planned"] = dict(
+            dev_rows, note="random batches without host lengths (plan kernel on the device); block_bound_grid passes "
+                           "total_blocks_bound = the batch's block count")
+        log(f"random, device-planned: {dev_rows}")
+
         # ---------------- batch generators: sort-and-chunk vs the paper's quad-tree DFS
         blocks_all = ((lens.astype(np.int64) + 15) // 16).astype(np.int32)
         b_max = int(0.4 * blocks_all.sum())          # 40 % of the pool's blocks (paper Section 4.1)

@@ -155,6 +155,14 @@ typedef struct {
                                  the library.  Otherwise a multiple of 16 in
                                  [16, 4096].                                         */
   int32_t flags;              /* AS_ATTN_* bits                                      */
+  int32_t total_blocks_bound; /* for calls WITHOUT kv_lens_host: the caller's upper
+                                 bound on the sum over the batch of ceil(kv_len / 16)
+                                 (a block allocator knows it exactly); the launch is
+                                 then sized for it instead of batch *
+                                 max_blocks_per_seq blocks.  0 => no bound.  If the
+                                 device lengths exceed it, the requests that do not
+                                 fit get wrong results (never a fault).  Ignored
+                                 when kv_lens_host is given.                         */
 } as_attn_params;
 
 /* The work plan in `workspace` was written by an earlier call with the same
@@ -167,9 +175,10 @@ typedef struct {
 
 /* Bytes of device workspace as_decode_attention needs for these parameters
  * when the batch holds at most total_kv_tokens tokens in all (sum of
- * kv_lens) AND the call passes kv_lens_host.  Pass total_kv_tokens < 0 to
- * size for the worst case batch * max_blocks_per_seq * 16, which also covers
- * calls without kv_lens_host.  Returns 0 on invalid parameters. */
+ * kv_lens) AND the call either passes kv_lens_host or sets
+ * total_blocks_bound <= total_kv_tokens / 16.  Pass total_kv_tokens < 0 to
+ * size for the worst case batch * max_blocks_per_seq * 16, which covers every
+ * call.  Returns 0 on invalid parameters. */
 size_t as_decode_attention_workspace(const as_attn_params* p, int64_t total_kv_tokens);
 
 /* q            device [batch][num_q_heads][head_dim], dtype

@@ -42,6 +42,7 @@ class AttnParams(C.Structure):
         ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("block_size", C.c_int32), ("num_blocks", C.c_int32), ("max_blocks_per_seq", C.c_int32),
         ("scale", C.c_float), ("chunk_tokens", C.c_int32), ("flags", C.c_int32),
+        ("total_blocks_bound", C.c_int32),
     ]
 
 
@@ -193,14 +194,15 @@ def _torch_dtype_code(t) -> int:
 
 
 def attn_params(q, k_blocks, block_table, out, scale: float = 0.0, chunk_tokens: int = 0,
-                flags: int = 0) -> AttnParams:
+                flags: int = 0, total_blocks_bound: int = 0) -> AttnParams:
     B, Hq, D = q.shape
     NB, Hkv, bs, D2 = k_blocks.shape
     assert D == D2
     return AttnParams(dtype=_torch_dtype_code(k_blocks), out_dtype=_torch_dtype_code(out), batch=B,
                       num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, block_size=bs, num_blocks=NB,
                       max_blocks_per_seq=block_table.shape[1], scale=float(scale),
-                      chunk_tokens=int(chunk_tokens), flags=int(flags))
+                      chunk_tokens=int(chunk_tokens), flags=int(flags),
+                      total_blocks_bound=int(total_blocks_bound))
 
 
 def decode_attention_workspace(params: AttnParams, total_kv_tokens: int = -1) -> int:
@@ -431,7 +433,7 @@ def kv_append(k_new, v_new, k_blocks, v_blocks, block_table, kv_lens, stream=Non
     params = AttnParams(dtype=_torch_dtype_code(k_blocks), out_dtype=_torch_dtype_code(k_blocks),
                         batch=kv_lens.shape[0], num_q_heads=Hkv, num_kv_heads=Hkv, head_dim=D,
                         block_size=bs, num_blocks=NB, max_blocks_per_seq=block_table.shape[1],
-                        scale=0.0, chunk_tokens=0, flags=0)
+                        scale=0.0, chunk_tokens=0, flags=0, total_blocks_bound=0)
     _check(load().as_kv_append(k_new.data_ptr(), v_new.data_ptr(), k_blocks.data_ptr(), v_blocks.data_ptr(),
                                block_table.data_ptr(), kv_lens.data_ptr(), C.byref(params),
                                _stream_ptr(stream)))

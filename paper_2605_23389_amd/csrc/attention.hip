@@ -172,7 +172,9 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ k
       s += nch;
     }
     const int c = static_cast<int>(i - f);
-    items[i] = make_int4(b, c, min(kv_lens[b], max_len), s + c);
+    // a slot beyond the partial-result arrays can only come from a caller's bound that the lengths
+    // exceed: the item is voided (length 0) instead of being allowed to write out of bounds
+    items[i] = make_int4(b, c, s + c < max_items ? min(kv_lens[b], max_len) : 0, s + c);
   }
   if (blockIdx.x != 0) return;
   // last chunks: class 0 holds the longest (tokens in the chunk from chunk down
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ k
   for (int b = lo; b < hi; ++b) {
     const int nch = chunks_of(b);
     const int64_t i = total_full + atomicAdd(&cls_next[class_of(b, nch)], 1);
-    if (i < n) items[i] = make_int4(b, nch - 1, min(kv_lens[b], max_len), s + nch - 1);
+    if (i < n) items[i] = make_int4(b, nch - 1, s + nch - 1 < max_items ? min(kv_lens[b], max_len) : 0, s + nch - 1);
     s += nch;
   }
 }
@@ -1028,7 +1030,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict_
                                                       const float2* __restrict__ part_ml,
                                                       const float* __restrict__ part_acc,
                                                       char* __restrict__ out, int batch, int Hq,
-                                                      int out_dtype) {
+                                                      int out_dtype, int max_items) {
   constexpr int LPP = D / 4;  // lanes per (request, head): an aligned group inside one wavefront
   const int pair = blockIdx.x * (256 / LPP) + threadIdx.x / LPP;
   const int sub = threadIdx.x % LPP;
@@ -1036,8 +1038,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t* __restrict_
   const int b = pair / Hq;
   const int hq = pair - b * Hq;
   const int first = use_inline ? icu.first[b] : cu_chunks[b];
-  const int n = (use_inline ? icu.first[b + 1] : cu_chunks[b + 1]) - first;
+  int n = (use_inline ? icu.first[b + 1] : cu_chunks[b + 1]) - first;
   if (n <= 1) return;  // finished by the attention kernel itself
+  if (first >= max_items) return;      // only when a caller's bound on the lengths did not hold:
+  n = min(n, max_items - first);       // stay inside the partial-result arrays
   // Few dependent memory round trips instead of one per chunk: lane `sub` fetches (m, l) of chunk
   // `sub`, the group's maximum and weights come from cross-lane steps, and the accumulator rows are
   // requested eight at a time before any of them is used.  More than LPP chunks: further rounds,
@@ -1259,6 +1263,8 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
     return als::fail(AS_EUNSUPPORTED, "%s: dtype %d / out_dtype %d", what, p->dtype, p->out_dtype);
   if (!(p->scale >= 0.f) || std::isinf(p->scale))
     return als::fail(AS_EINVAL, "%s: scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))", what);
+  if (p->total_blocks_bound < 0)
+    return als::fail(AS_EINVAL, "%s: total_blocks_bound %d is negative", what, p->total_blocks_bound);
   if (p->chunk_tokens != 0 &&
       (p->chunk_tokens < kBlock || p->chunk_tokens > kMaxChunk || p->chunk_tokens % kBlock))
     return als::fail(AS_EINVAL, "%s: chunk_tokens %d must be 0 or a multiple of 16 in [16, %d]", what,
@@ -1274,6 +1280,9 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
     }
   } else {
     total = cap * p->batch;
+    // the caller's promise on the sum of the lengths (in blocks) sizes the launch instead of the worst case
+    if (p->total_blocks_bound > 0 && static_cast<int64_t>(p->total_blocks_bound) * kBlock < total)
+      total = static_cast<int64_t>(p->total_blocks_bound) * kBlock;
   }
   out->total_tokens = total;
   out->chunk = pick_chunk(*p, total);
@@ -1318,7 +1327,9 @@ as_status validate(const char* what, const as_attn_params* p, const int32_t* kv_
     out->items = items;
     out->any_split = split;
   } else {
-    out->items = static_cast<int64_t>(p->batch) * ((cap + out->chunk - 1) / out->chunk);
+    // every request contributes ceil(L / chunk) <= L / chunk + 1 items
+    out->items = std::min(static_cast<int64_t>(p->batch) * ((cap + out->chunk - 1) / out->chunk),
+                          total / out->chunk + p->batch);
   }
   out->w = layout_for(*p, out->items);
   // small launches with known lengths: build the plan here and ship it in the
@@ -1509,12 +1520,13 @@ as_status run_decode_attention(const char* what, const void* q, const void* k_bl
     const int pairs = p->batch * p->num_q_heads;
     const dim3 cgrid((pairs + pairs_per_block - 1) / pairs_per_block);
     const int32_t* cu = reinterpret_cast<const int32_t*>(ws + ck.w.cu_off);
+    const int max_items = static_cast<int>(ck.w.max_items < 0x7FFFFFFF ? ck.w.max_items : 0x7FFFFFFF);
     if (p->head_dim == 128)
       hipLaunchKernelGGL(combine_kernel<128>, cgrid, dim3(256), 0, s, cu, ck.icu, int(ck.use_inline), a.part_ml, a.part_acc,
-                         a.out, p->batch, p->num_q_heads, a.out_dtype);
+                         a.out, p->batch, p->num_q_heads, a.out_dtype, max_items);
     else
       hipLaunchKernelGGL(combine_kernel<64>, cgrid, dim3(256), 0, s, cu, ck.icu, int(ck.use_inline), a.part_ml, a.part_acc,
-                         a.out, p->batch, p->num_q_heads, a.out_dtype);
+                         a.out, p->batch, p->num_q_heads, a.out_dtype, max_items);
     ALS_HIP_CHECK(hipGetLastError());
   }
   return AS_OK;

@@ -282,3 +282,31 @@ def test_one_very_long_request(lib):
     _check(lib, pb, out_dtype="fp32", chunk_tokens=4096)
     pb = wl.make_paged_batch(lens, 8, 1, 128, dtype="bf16", seed=94, poison="nan")     # matrix-core kernel
     _check(lib, pb, out_dtype="fp32")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2)])
+def test_device_plan_sized_by_a_block_bound(lib, Hq, Hkv):
+    """Calls without host lengths may carry the caller's bound on the number of blocks the batch
+    holds: the launch is sized for it instead of batch * row length.  Exact bound, generous bound,
+    a wide block table (so that the worst case is far larger), split and unsplit requests."""
+    import torch
+    from paper_2605_23389_amd import binding as als
+    rng = np.random.default_rng(314)
+    lens = np.concatenate([rng.integers(1, 3000, 20), [1, 16, 17, 4096]]).astype(np.int32)
+    pb = wl.make_paged_batch(lens, Hq, Hkv, 128, dtype="bf16", seed=314, poison="nan", spare_blocks=1,
+                             extra_table_cols=300)
+    ref = oracle_out(pb)
+    d = to_device(pb)
+    exact = int(((lens.astype(np.int64) + 15) // 16).sum())
+    for bound in (exact, 3 * exact):
+        for chunk in (0, 64):
+            out = torch.full(d["q"].shape, float("nan"), dtype=torch.float32, device="cuda")
+            params = als.attn_params(d["q"], d["k"], d["bt"], out, chunk_tokens=chunk, total_blocks_bound=bound)
+            ws = torch.empty(lib.decode_attention_workspace(params, bound * 16), dtype=torch.uint8, device="cuda")
+            assert ws.numel() < lib.decode_attention_workspace(params, -1)
+            lib.decode_attention(d["q"], d["k"], d["v"], d["bt"], d["lens"], out, workspace=ws, params=params)
+            torch.cuda.synchronize()
+            check_parity(out.double().cpu().numpy(), ref, pb, out_dtype="fp32", what=f"bound {bound} chunk {chunk}")
+    params = als.attn_params(d["q"], d["k"], d["bt"], out, total_blocks_bound=-1)
+    with pytest.raises(als.AlignedServeError):
+        lib.decode_attention(d["q"], d["k"], d["v"], d["bt"], d["lens"], out, params=params)
