@@ -348,7 +348,7 @@ class DecodeSim:
         self.first_admitted: Dict[int, int] = {}                  # rid -> iteration of its first admission
         self.run_ids = np.zeros(0, dtype=np.int32)
         self.stats = dict(attn_us=[], fwd_us=[], gap_us=[], batch_size=[], tokens=[], sched_ms=[], switching=0,
-                          evictions=0, admissions=0, admitted_prefetched=0, admitted_resident=0, trace=[], completed=0, restored_blocks=0,
+                          evictions=0, admissions=0, admitted_prefetched=0, admitted_resident=0, completed=0, restored_blocks=0,
                           evicted_blocks=0, eviction_lens=[])
         self.be = _DryBackend(self) if cfg.dry else _GpuBackend(self)
 
@@ -529,11 +529,8 @@ class DecodeSim:
             for r in evicted:
                 self._evict(r)
             self._reclaim(wait=False)
-            res0, pre0 = self.stats["admitted_resident"], self.stats["admitted_prefetched"]
             if admitted:
                 self._admit(admitted)
-            self.stats["trace"].append((len(done), len(evicted), len(admitted), self.stats["admitted_prefetched"] - pre0,
-                                        self.stats["admitted_resident"] - res0, case))
             if cfg.prefetch:
                 self._prefetch_tick()
             ids, lens, origins = self.sched.running()
