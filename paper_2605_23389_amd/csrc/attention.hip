@@ -459,6 +459,17 @@ __device__ __forceinline__ void load_tile(u32x4 (&r)[kBlock * D * sizeof(T) / 10
   for (int i = 0; i < NLD; ++i) r[i] = load128(p + i * 1024);
 }
 
+// The same with ordinary loads, which the caches may retain: for launches in which several
+// workgroups (slices of one wide group of query heads) read the same KV head's stream side by side.
+template <typename T, int D>
+__device__ __forceinline__ void load_tile_shared(u32x4 (&r)[kBlock * D * sizeof(T) / 1024], const char* slab,
+                                                 int lane) {
+  constexpr int NLD = kBlock * D * sizeof(T) / 1024;
+  const char* p = slab + lane * 16;
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) r[i] = *reinterpret_cast<const u32x4*>(p + i * 1024);
+}
+
 // merge state `o` (from another token group / wave) into `s`; both in raw-max units
 template <int EPL>
 __device__ __forceinline__ void merge_state(HeadState<EPL>& s, float om, float ol, const float (&oacc)[EPL],
@@ -682,7 +693,10 @@ constexpr int kMfmaHeads = 16;      // query heads per MFMA column block
 #ifndef AS_MFMA_MAX_HEADS
 #define AS_MFMA_MAX_HEADS 32
 #endif
-constexpr int kMfmaMaxHeads = AS_MFMA_MAX_HEADS;  // query heads one workgroup serves (1 or 2 column blocks)
+constexpr int kMfmaMaxHeads = AS_MFMA_MAX_HEADS;
+#ifndef AS_SHARED_LOADS
+#define AS_SHARED_LOADS true
+#endif  // query heads one workgroup serves (1 or 2 column blocks)
 
 // The two 16-bit element types differ only in the MFMA opcodes and in how
 // probabilities are rounded to the element type and widened back.
@@ -823,7 +837,7 @@ __device__ __forceinline__ void mfma_tile(const u32x4 (&kr)[4], const u32x4 (&vr
 }
 
 // G = query heads per workgroup (<= 16 * NG), D = 128, T = bf16_t or f16_t.
-template <typename T, int NG>
+template <typename T, int NG, bool SHARED = false>
 __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, InlinePlan ip) {
   constexpr int D = 128;
   constexpr int kHeads = kMfmaHeads * NG;
@@ -918,13 +932,17 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   const size_t block_stride = static_cast<size_t>(Hkv) * kSlabBytes;
 
   u32x4 kA[4], vA[4], kB[4], vB[4];
+  auto ld = [&](u32x4 (&r)[4], const char* slab) {
+    if constexpr (SHARED) load_tile_shared<T, D>(r, slab, lane);
+    else load_tile<T, D>(r, slab, lane);
+  };
   auto tile_off = [&](int i) {
     return static_cast<size_t>(__builtin_amdgcn_readlane(my_id, i)) * block_stride + head_off;
   };
   if (my_tiles > 0) {
     const size_t off = tile_off(0);
-    load_tile<T, D>(kA, a.k_blocks + off, lane);
-    load_tile<T, D>(vA, a.v_blocks + off, lane);
+    ld(kA, a.k_blocks + off);
+    ld(vA, a.v_blocks + off);
   }
   // Only the chunk's last tile can be partial.  The hot loop takes pairs of
   // full tiles with the unmasked code; at most two tiles are left for the
@@ -935,14 +953,14 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
   for (; i + 2 <= full_tiles; i += 2) {
     {
       const size_t off = tile_off(i + 1);
-      load_tile<T, D>(kB, a.k_blocks + off, lane);
-      load_tile<T, D>(vB, a.v_blocks + off, lane);
+      ld(kB, a.k_blocks + off);
+      ld(vB, a.v_blocks + off);
     }
     mfma_tile<T, false, NG>(kA, vA, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
     if (i + 2 < my_tiles) {
       const size_t off = tile_off(i + 2);
-      load_tile<T, D>(kA, a.k_blocks + off, lane);
-      load_tile<T, D>(vA, a.v_blocks + off, lane);
+      ld(kA, a.k_blocks + off);
+      ld(vA, a.v_blocks + off);
     }
     mfma_tile<T, false, NG>(kB, vB, qb, lds, acc, m_run, l_run, c, 0, 0, lane);
   }
@@ -950,8 +968,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, int G, 
     const bool haveB = i + 1 < my_tiles;
     if (haveB) {
       const size_t off = tile_off(i + 1);
-      load_tile<T, D>(kB, a.k_blocks + off, lane);
-      load_tile<T, D>(vB, a.v_blocks + off, lane);
+      ld(kB, a.k_blocks + off);
+      ld(vB, a.v_blocks + off);
     }
     mfma_tile<T, true, NG>(kA, vA, qb, lds, acc, m_run, l_run, c, t0 + (wave + kWaves * i) * kBlock, kv_len, lane);
     if (haveB)
@@ -1486,16 +1504,26 @@ as_status run_decode_attention(const char* what, const void* q, const void* k_bl
     a.head_groups = p->num_q_heads / mfma_heads;
     a.kv_div = group / mfma_heads;
     const dim3 grid(static_cast<unsigned>(ck.items * a.head_groups));
-    if (mfma_heads <= kMfmaHeads) {
+    if (mfma_heads <= kMfmaHeads && a.kv_div == 1) {
       if (p->dtype == AS_DTYPE_BF16)
         hipLaunchKernelGGL((attn_mfma_kernel<bf16_t, 1>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
       else
         hipLaunchKernelGGL((attn_mfma_kernel<f16_t, 1>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
-    } else {
+    } else if (mfma_heads <= kMfmaHeads) {  // slices of 16 or 8 heads side by side on one KV head
+      if (p->dtype == AS_DTYPE_BF16)
+        hipLaunchKernelGGL((attn_mfma_kernel<bf16_t, 1, AS_SHARED_LOADS>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+      else
+        hipLaunchKernelGGL((attn_mfma_kernel<f16_t, 1, AS_SHARED_LOADS>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+    } else if (a.kv_div == 1) {
       if (p->dtype == AS_DTYPE_BF16)
         hipLaunchKernelGGL((attn_mfma_kernel<bf16_t, 2>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
       else
         hipLaunchKernelGGL((attn_mfma_kernel<f16_t, 2>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+    } else {  // several slices of 32 heads read the same KV head: loads that the caches may keep
+      if (p->dtype == AS_DTYPE_BF16)
+        hipLaunchKernelGGL((attn_mfma_kernel<bf16_t, 2, AS_SHARED_LOADS>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
+      else
+        hipLaunchKernelGGL((attn_mfma_kernel<f16_t, 2, AS_SHARED_LOADS>), grid, dim3(kThreads), 0, s, a, mfma_heads, ck.ip);
     }
   } else {
     const int G = kc.heads;
