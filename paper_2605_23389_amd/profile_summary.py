@@ -2,7 +2,7 @@
 FETCH_SIZE, WRITE_SIZE) into the short summary under profiles/ and into the
 HBM-traffic figure bench.py reports as roofline.traffic.
 
-    python -m paper_2605_23389_amd.profile_summary --dir gpurun_out/prof_cfg2 \\
+    python -m paper_2605_23389_amd.profile_summary --dir <raw-output-dir> \\
         --kernel attn_kernel --alg-bytes 1969799885 --out profiles/attn_bf16_d128_cfg2_aligned.md \\
         --json-key attn_cfg2_aligned_bytes_per_launch --title "..." --bench-args "" --note "..."
 
