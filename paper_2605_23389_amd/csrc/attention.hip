@@ -1470,12 +1470,12 @@ namespace {
 
 // Shared body of as_decode_attention and as_decode_attention_static: argument
 // checks, then the plan / attention / combine launches on `ws`.
-as_status run_decode_attention(const char* what, const void* q, const void* k_blocks,
-                               const void* v_blocks, const int32_t* block_table,
-                               const int32_t* kv_lens, const int32_t* kv_lens_host, void* out,
-                               const as_attn_params* p, void* workspace, size_t workspace_bytes,
-                               void* hip_stream) {
-  if (!q || !k_blocks || !v_blocks || !block_table || !kv_lens || !out || !workspace)
+// Host-side argument checks of a decode-attention call (no GPU call is made); fills `ck`.
+as_status check_decode_args(const char* what, const void* q, const void* k_blocks, const void* v_blocks,
+                            const int32_t* block_table, const int32_t* kv_lens,
+                            const int32_t* kv_lens_host, const void* out, const as_attn_params* p,
+                            Checked* ck) {
+  if (!q || !k_blocks || !v_blocks || !block_table || !kv_lens || !out)
     return als::fail(AS_EINVAL, "%s: a required pointer is null", what);
   // the kernels move q, K, V and the result with 128-bit accesses
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_blocks) |
@@ -1483,9 +1483,29 @@ as_status run_decode_attention(const char* what, const void* q, const void* k_bl
     return als::fail(AS_EINVAL, "%s: q, k_blocks, v_blocks and out must be 16-byte aligned", what);
   if ((reinterpret_cast<uintptr_t>(block_table) | reinterpret_cast<uintptr_t>(kv_lens)) % 4)
     return als::fail(AS_EINVAL, "%s: block_table and kv_lens must be 4-byte aligned", what);
-  Checked ck;
-  as_status st = validate(what, p, kv_lens_host, workspace_bytes, workspace, &ck);
-  if (st != AS_OK) return st;
+  return validate(what, p, kv_lens_host, 0, nullptr, ck);
+}
+
+as_status run_decode_attention(const char* what, const void* q, const void* k_blocks,
+                               const void* v_blocks, const int32_t* block_table,
+                               const int32_t* kv_lens, const int32_t* kv_lens_host, void* out,
+                               const as_attn_params* p, void* workspace, size_t workspace_bytes,
+                               void* hip_stream, const Checked* checked = nullptr) {
+  if (!workspace)
+    return als::fail(AS_EINVAL, "%s: a required pointer is null", what);
+  Checked local;
+  if (!checked) {
+    const as_status st0 = check_decode_args(what, q, k_blocks, v_blocks, block_table, kv_lens, kv_lens_host, out, p,
+                                            &local);
+    if (st0 != AS_OK) return st0;
+    checked = &local;
+  }
+  const Checked& ck = *checked;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256)
+    return als::fail(AS_EINVAL, "%s: workspace is not 256-byte aligned", what);
+  if (workspace_bytes < ck.w.total)
+    return als::fail(AS_EWORKSPACE, "%s: workspace has %zu bytes, needs %zu", what, workspace_bytes, ck.w.total);
+  as_status st = AS_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   // When the host lengths show that no request needs more than one chunk,
@@ -1612,13 +1632,19 @@ extern "C" as_status as_decode_attention_static(const void* q, const void* k_blo
                                                 const void* v_blocks, const int32_t* block_table,
                                                 const int32_t* kv_lens, const int32_t* kv_lens_host,
                                                 void* out, const as_attn_params* p, void* hip_stream) {
-  void* ws = nullptr;
-  const as_status st = static_scratch(&ws);
+  // argument errors, and a plan + partials larger than the array, are reported before any GPU call
+  Checked ck;
+  as_status st = check_decode_args("as_decode_attention_static", q, k_blocks, v_blocks, block_table, kv_lens,
+                                   kv_lens_host, out, p, &ck);
   if (st != AS_OK) return st;
-  // validate() turns a plan + partials larger than the array into AS_EWORKSPACE
-  // before anything is enqueued
+  if (ck.w.total > AS_STATIC_SCRATCH_BYTES)
+    return als::fail(AS_EWORKSPACE, "as_decode_attention_static: plan and partials need %zu bytes, the static array has %u",
+                     ck.w.total, static_cast<unsigned>(AS_STATIC_SCRATCH_BYTES));
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != AS_OK) return st;
   return run_decode_attention("as_decode_attention_static", q, k_blocks, v_blocks, block_table, kv_lens,
-                              kv_lens_host, out, p, ws, AS_STATIC_SCRATCH_BYTES, hip_stream);
+                              kv_lens_host, out, p, ws, AS_STATIC_SCRATCH_BYTES, hip_stream, &ck);
 }
 
 extern "C" as_status as_kv_read_sweep(const void* k_blocks, const void* v_blocks,

@@ -123,6 +123,28 @@ def test_decode_attention_argument_errors_before_any_gpu_work(lib):
     assert "16-byte aligned" in handle.as_last_error().decode()
 
 
+def test_static_entry_reports_argument_errors_before_any_gpu_call(lib):
+    """The entry point for callers that cannot allocate checks its arguments -- and whether the plan
+    fits the static array -- on the host, before it even looks the array up on the device."""
+    handle = lib.load()
+    fake = C.c_void_p(0x1000)
+    lens = np.array([5, 6, 7, 8], dtype=np.int32)
+
+    def call(p, host=lens, q=fake):
+        hp = None if host is None else host.ctypes.data_as(C.POINTER(C.c_int32))
+        return handle.as_decode_attention_static(q, fake, fake, fake, fake, hp, fake, C.byref(p), None)
+
+    assert call(_params(), q=None) == als.AS_EINVAL
+    assert call(_params(head_dim=96)) == als.AS_EUNSUPPORTED
+    assert call(_params(), host=np.array([5, 0, 7, 8], dtype=np.int32)) == als.AS_ERANGE
+    assert call(_params(total_blocks_bound=-3), host=None) == als.AS_EINVAL
+    # 4 requests x 2048 blocks, 16-token chunks, 64 heads: the partials alone are far beyond 32 MiB
+    big = _params(num_q_heads=64, num_kv_heads=8, head_dim=128, max_blocks_per_seq=2048, chunk_tokens=16)
+    assert call(big, host=np.full(4, 32768, dtype=np.int32)) == als.AS_EWORKSPACE
+    assert "static array" in handle.as_last_error().decode()
+    assert handle.as_decode_attention_static_capacity() == 32 << 20
+
+
 def test_workspace_size_query(lib):
     p = _params()
     worst = lib.decode_attention_workspace(p, -1)
