@@ -310,3 +310,27 @@ def test_device_plan_sized_by_a_block_bound(lib, Hq, Hkv):
     params = als.attn_params(d["q"], d["k"], d["bt"], out, total_blocks_bound=-1)
     with pytest.raises(als.AlignedServeError):
         lib.decode_attention(d["q"], d["k"], d["v"], d["bt"], d["lens"], out, params=params)
+
+
+def test_device_length_beyond_the_table_row_is_cut_to_it(lib):
+    """Without host lengths nothing is validated: a device length larger than the block-table
+    row can hold is cut to the row (documented: a wrong answer for that request, never a read
+    outside its row), and the other requests are unaffected."""
+    import torch
+    lens = np.array([48, 80, 33], dtype=np.int32)
+    pb = wl.make_paged_batch(lens, 4, 2, 128, dtype="bf16", seed=55, spare_blocks=1)
+    cap = pb.block_table.shape[1] * 16
+    assert cap == 80
+    d = to_device(pb)
+    d["lens"][0] = cap + 1000                     # request 0 claims more than its row holds
+    out = torch.full(d["q"].shape, float("nan"), dtype=torch.float32, device="cuda")
+    lib.decode_attention(d["q"], d["k"], d["v"], d["bt"], d["lens"], out, chunk_tokens=32)
+    torch.cuda.synchronize()
+    got = out.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    ref = oracle_out(pb)
+    assert np.abs(got[1:] - ref[1:]).max() <= 1e-5
+    # request 0: attention over the whole row (its own 48 tokens, then the row's remaining entries)
+    pb.kv_lens = np.array([cap, 80, 33], dtype=np.int32)
+    ref_cut = oracle_out(pb)
+    assert np.abs(got[0] - ref_cut[0]).max() <= 1e-5
