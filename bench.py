@@ -686,7 +686,7 @@ def main():
 
     if not args.skip_extra:
         # ---------------- per-batch times, aligned vs random
-        def per_batch(batches, reps=9, fn=None):
+        def per_batch(batches, reps=15, fn=None):
             """Every batch timed inside passes over all of them (31.6 GB cycled: nothing is re-read from
             the 256 MB Infinity Cache, as it would be if one small batch were launched back to back);
             median over the passes.  The event pair around a launch adds about 1.7 us to it."""
@@ -699,9 +699,11 @@ def main():
             torch.cuda.synchronize()
             rows = []
             for i, b in enumerate(batches):
-                s = float(np.median([ev[r][i].elapsed_time(ev[r][i + 1]) for r in range(reps)])) / 1e3
+                ts = np.array([ev[r][i].elapsed_time(ev[r][i + 1]) for r in range(reps)]) * 1e3   # us
+                s = float(np.median(ts)) / 1e6
                 rows.append({"tokens": b.tokens, "max_len": int(b.kv_lens_host.max()),
-                             "us": round(s * 1e6, 1), "GBs": round(b.bytes / s / 1e9, 0),
+                             "us": round(s * 1e6, 1), "us_p10": round(float(np.percentile(ts, 10)), 1),
+                             "us_p90": round(float(np.percentile(ts, 90)), 1), "GBs": round(b.bytes / s / 1e9, 0),
                              "pct_of_peak": round(b.bytes / s / 1e9 / HBM_PEAK_GBS * 100, 1)})
             return rows
 
