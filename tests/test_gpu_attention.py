@@ -334,3 +334,21 @@ def test_device_length_beyond_the_table_row_is_cut_to_it(lib):
     pb.kv_lens = np.array([cap, 80, 33], dtype=np.int32)
     ref_cut = oracle_out(pb)
     assert np.abs(got[0] - ref_cut[0]).max() <= 1e-5
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype", [(4, 4, "fp32"), (4, 4, "bf16"), (8, 1, "bf16"), (32, 1, "bf16")])
+def test_peaked_and_flat_softmax_at_length(lib, Hq, Hkv, dtype):
+    """The two ends of the softmax: scale 1 (scores with a spread of about +-35, weights close to
+    one-hot, outputs of order 1 -- the running maximum moves often and rescaling matters) and
+    scale 1e-3 (weights almost uniform over thousands of tokens -- the sum l is large), through
+    split and unsplit launches of both kernels."""
+    lens = np.array([5000, 1, 777, 4096, 18], dtype=np.int32)
+    pb = wl.make_paged_batch(lens, Hq, Hkv, 128, dtype=dtype, seed=808, poison="nan", spare_blocks=1)
+    dev = to_device(pb)
+    for scale in (1.0, 1e-3):
+        ref = oracle_out(pb, scale=scale)
+        for chunk in (0, 256):
+            got = run_attention(lib, pb, out_dtype="fp32", chunk_tokens=chunk, scale=scale, dev=dev)
+            check_parity(got, ref, pb, out_dtype="fp32", what=f"scale {scale} chunk {chunk}")
+    peaked = oracle_out(pb, scale=1.0)
+    assert np.abs(peaked[0]).max() > 0.5          # the peaked case really is near one-hot: outputs of order 1
