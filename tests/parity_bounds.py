@@ -59,6 +59,8 @@ def assert_parity(got: np.ndarray, ref: np.ndarray, dtype: str, out_dtype: str, 
     excess = err - elementwise_bound(ref, dtype, out_dtype, matrix_core)
     assert (excess <= 0).all(), (f"{what}: max-abs err {worst:.3e}, over the "
                                  f"{'matrix-core' if matrix_core else 'vector'} bound by {float(excess.max()):.3e}")
-    if dtype in CONTRACT:
+    # the contract for fp32 inputs (1e-5) is stated for fp32 results; a 16-bit result of fp32
+    # inputs carries its output rounding, which the element-wise bound above already limits
+    if dtype in CONTRACT and not (dtype == "fp32" and out_dtype != "fp32"):
         assert worst <= CONTRACT[dtype], f"{what}: max-abs err {worst:.3e} over the contract"
     return worst

@@ -352,3 +352,14 @@ def test_peaked_and_flat_softmax_at_length(lib, Hq, Hkv, dtype):
             check_parity(got, ref, pb, out_dtype="fp32", what=f"scale {scale} chunk {chunk}")
     peaked = oracle_out(pb, scale=1.0)
     assert np.abs(peaked[0]).max() > 0.5          # the peaked case really is near one-hot: outputs of order 1
+
+
+@pytest.mark.parametrize("dtype,out_dtype", [("bf16", "fp16"), ("fp32", "bf16"), ("fp32", "fp16")])
+def test_output_type_is_independent_of_the_input_type(lib, dtype, out_dtype):
+    lens = np.array([1, 40, 300, 1025], dtype=np.int32)
+    for Hq, Hkv in ((4, 4), (8, 1)):
+        pb = wl.make_paged_batch(lens, Hq, Hkv, 128, dtype=dtype, seed=99, poison="nan", spare_blocks=1)
+        ref = oracle_out(pb)
+        for chunk in (0, 128):
+            got = run_attention(lib, pb, out_dtype=out_dtype, chunk_tokens=chunk)
+            check_parity(got, ref, pb, out_dtype=out_dtype, what=f"{dtype}->{out_dtype} {Hq}/{Hkv} chunk {chunk}")
